@@ -1,0 +1,307 @@
+"""Pins of the CPU oracle against things other than itself: textbook dense attention written in numpy,
+algebraic invariants, closed forms, brute force on tiny inputs and the values the paper prints."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_00868_amd import synth
+
+GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.json")))
+
+
+def widen(bits):
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def rand_bf16(rng, shape, scale=1.0):
+    return synth.f32_to_bf16_bits((rng.standard_normal(shape) * scale).astype(np.float32))
+
+
+def dense_attention_numpy(q, k, v, ctx, scale):
+    """Textbook softmax attention in numpy fp64 over tokens [0, ctx)."""
+    qf, kf, vf = widen(q), widen(k[:ctx]), widen(v[:ctx])
+    z = scale * (kf @ qf)
+    w = np.exp(z - z.max())
+    w /= w.sum()
+    return w @ vf, float(z.max() + np.log(np.exp(z - z.max()).sum()))
+
+
+# ---- P1 / P2: attention -----------------------------------------------------------------------
+@pytest.mark.parametrize("ctx", [1, 5, 16, 17, 100, 256])
+def test_all_pages_equals_dense_attention(ctx):
+    rng = np.random.default_rng(ctx)
+    D, P = 128, 16
+    n = -(-ctx // P)
+    k, v = rand_bf16(rng, (n * P, D)), rand_bf16(rng, (n * P, D))
+    k[ctx:] = 0x7FC0   # NaN beyond the context: must never be read
+    v[ctx:] = 0x7FC0
+    q = rand_bf16(rng, (D,))
+    scale = 1 / np.sqrt(D)
+    out, lse, ws = oracle.attention(q, k, v, ctx, np.arange(n), scale)
+    ref, ref_lse = dense_attention_numpy(q, k, v, ctx, scale)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+    assert abs(lse - ref_lse) < 1e-12
+    assert abs(ws - 1.0) < 1e-12
+    vf = widen(v[:ctx])
+    assert np.all(out <= vf.max(0) + 1e-12) and np.all(out >= vf.min(0) - 1e-12)  # convex hull of V rows
+
+
+def test_page_subset_equals_dense_attention_over_those_tokens():
+    rng = np.random.default_rng(7)
+    D, P, ctx = 128, 16, 200
+    n = -(-ctx // P)
+    k, v, q = rand_bf16(rng, (n * P, D)), rand_bf16(rng, (n * P, D)), rand_bf16(rng, (D,))
+    pages = np.array([12, 3, 7])          # order must not matter; page 12 is partial (tokens 192..199)
+    toks = np.concatenate([np.arange(p * P, min((p + 1) * P, ctx)) for p in pages])
+    out, lse, ws = oracle.attention(q, k, v, ctx, pages, 0.125)
+    ref, ref_lse = dense_attention_numpy(q, k[toks], v[toks], len(toks), 0.125)
+    np.testing.assert_allclose(out, ref, rtol=1e-12, atol=1e-13)
+    out2, lse2, _ = oracle.attention(q, k, v, ctx, np.sort(pages), 0.125)
+    np.testing.assert_allclose(out, out2, rtol=1e-13, atol=1e-14)
+    assert abs(lse - ref_lse) < 1e-12 and abs(ws - 1) < 1e-12
+
+
+def test_one_hot_value_recovers_softmax_weight():
+    """V = indicator of token j in dim 0 makes out[0] the softmax weight of token j."""
+    rng = np.random.default_rng(3)
+    D, P, ctx = 128, 16, 64
+    k, q = rand_bf16(rng, (ctx, D)), rand_bf16(rng, (D,))
+    j = 37
+    v = np.zeros((ctx, D), dtype=np.uint16)
+    v[j, 0] = 0x3F80  # 1.0
+    out, _, _ = oracle.attention(q, k, v, ctx, np.arange(4), 0.3)
+    z = 0.3 * (widen(k) @ widen(q))
+    w = np.exp(z - z.max()); w /= w.sum()
+    assert abs(out[0] - w[j]) < 1e-14 and np.all(out[1:] == 0)
+
+
+# ---- P3: split + log-sum-exp merge --------------------------------------------------------------
+def test_any_partition_of_the_page_set_merges_to_the_same_result():
+    rng = np.random.default_rng(11)
+    D, P, ctx = 128, 16, 333
+    n = -(-ctx // P)
+    k, v, q = rand_bf16(rng, (n * P, D)), rand_bf16(rng, (n * P, D)), rand_bf16(rng, (D,), 2.0)
+    scale = 1 / np.sqrt(D)
+    full, full_lse, _ = oracle.attention(q, k, v, ctx, np.arange(n), scale)
+    for trial in range(5):
+        perm = rng.permutation(n)
+        cuts = np.sort(rng.choice(np.arange(1, n), size=rng.integers(1, 6), replace=False))
+        parts = np.split(perm, cuts)
+        outs, lses = zip(*[oracle.attention(q, k, v, ctx, p, scale)[:2] for p in parts])
+        m = max(lses)
+        wts = np.exp(np.array(lses) - m)
+        merged = sum(w * o for w, o in zip(wts, outs)) / wts.sum()
+        np.testing.assert_allclose(merged, full, rtol=1e-12, atol=1e-13)
+        assert abs(m + np.log(wts.sum()) - full_lse) < 1e-12
+
+
+# ---- P4 / P5: page score ------------------------------------------------------------------------
+def test_minmax_is_min_and_max_over_valid_tokens():
+    rng = np.random.default_rng(5)
+    D, P, ctx = 128, 16, 70
+    n = -(-ctx // P)
+    k = rand_bf16(rng, (n * P, D))
+    k[ctx:] = 0x7FC0
+    mm = oracle.build_minmax(k, ctx, P)
+    kf = widen(k)
+    for p in range(n):
+        rows = kf[p * P:min((p + 1) * P, ctx)]
+        np.testing.assert_array_equal(widen(mm[p, 0]), rows.min(0))
+        np.testing.assert_array_equal(widen(mm[p, 1]), rows.max(0))
+
+
+def test_score_upper_bounds_every_dot_product_and_is_tight_for_single_key_pages():
+    rng = np.random.default_rng(9)
+    D, P, G, ctx = 128, 16, 4, 16 * 12 + 1     # last page holds exactly one key
+    n = -(-ctx // P)
+    k = rand_bf16(rng, (n * P, D))
+    k[16:32] = k[16]                           # page 1: sixteen identical keys
+    q = rand_bf16(rng, (G, D))
+    mm = oracle.build_minmax(k, ctx, P)
+    s = oracle.page_scores(q, mm)
+    dots = widen(k[:ctx]) @ widen(q).T          # [tokens, G]
+    for p in range(n):
+        rows = dots[p * P:min((p + 1) * P, ctx)]
+        assert s[p] >= rows.max() - 1e-9
+    assert abs(s[n - 1] - dots[ctx - 1].max()) < 1e-9        # one key: bound is exact
+    assert abs(s[1] - dots[16].max()) < 1e-9                 # identical keys: bound is exact
+    assert np.sum(s > np.array([dots[p * P:min((p + 1) * P, ctx)].max() for p in range(n)]) + 1e-6) >= n - 2
+
+
+def test_score_closed_forms_and_homogeneity():
+    rng = np.random.default_rng(13)
+    D, P, ctx = 128, 16, 160
+    k = rand_bf16(rng, (ctx, D))
+    mm = oracle.build_minmax(k, ctx, P)
+    lo, hi = widen(mm[:, 0]), widen(mm[:, 1])
+    qpos = synth.f32_to_bf16_bits(np.abs(rng.standard_normal((1, D))).astype(np.float32))
+    qneg = qpos | np.uint16(0x8000)
+    np.testing.assert_allclose(oracle.page_scores(qpos, mm), hi @ widen(qpos[0]), rtol=1e-13)
+    np.testing.assert_allclose(oracle.page_scores(qneg, mm), lo @ widen(qneg[0]), rtol=1e-13)
+    q = rand_bf16(rng, (1, D))
+    q4 = synth.f32_to_bf16_bits(4.0 * synth.bf16_bits_to_f32(q))   # exact power-of-two scaling
+    np.testing.assert_allclose(oracle.page_scores(q4, mm), 4 * oracle.page_scores(q, mm), rtol=1e-13)
+    # mixed-sign definition, retyped independently as a masked sum
+    qf = widen(q[0])
+    ref = np.where(qf >= 0, hi * qf, lo * qf).sum(1)
+    np.testing.assert_allclose(oracle.page_scores(q, mm), ref, rtol=1e-12)
+
+
+def test_group_combination_is_max_over_the_group_with_sum_as_audit_mode():
+    rng = np.random.default_rng(17)
+    D, P, ctx, G = 128, 16, 96, 4
+    k, q = rand_bf16(rng, (ctx, D)), rand_bf16(rng, (G, D))
+    mm = oracle.build_minmax(k, ctx, P)
+    per = np.stack([oracle.page_scores(q[g:g + 1], mm) for g in range(G)])
+    np.testing.assert_array_equal(oracle.page_scores(q, mm, 0), per.max(0))
+    np.testing.assert_allclose(oracle.page_scores(q, mm, 1), per.sum(0), rtol=1e-13)
+
+
+# ---- P6: selection ------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,K,ctx_mod", [(1, 1, 0), (8, 3, 0), (8, 3, 5), (8, 8, 0), (8, 20, 3),
+                                         (128, 8, 0), (300, 37, 9), (2048, 204, 0)])
+def test_selection_equals_lexsort(n, K, ctx_mod):
+    rng = np.random.default_rng(n * 31 + K)
+    P = 16
+    ctx = n * P if ctx_mod == 0 else (n - 1) * P + ctx_mod
+    s = rng.standard_normal(n)
+    s[rng.integers(0, n, size=n // 3)] = 0.25       # many exact ties
+    got = oracle.select_topk(s, ctx, K, P)
+    want = min(K, n)
+    forced = [n - 1] if ctx_mod else []
+    rest = [p for p in np.lexsort((np.arange(n), -s)) if p not in forced]   # score desc, index asc
+    ref = sorted(forced + rest[:want - len(forced)])
+    assert list(got) == ref
+    assert len(got) == want and np.all(np.diff(got) > 0)
+
+
+def test_planted_hot_pages_are_selected():
+    cfg = synth.make_config(1)
+    w = synth.Workload(cfg)
+    q = w.queries(0)
+    for h in range(cfg.num_kv_heads):
+        mm = oracle.build_minmax(w.k[0][h], cfg.ctx[0])
+        s = oracle.page_scores(q[0, h * cfg.group:(h + 1) * cfg.group], mm)
+        sel = oracle.select_topk(s, cfg.ctx[0], 8)
+        assert set(w.hot[(0, h)]) <= set(int(x) for x in sel)
+
+
+# ---- P7: promotion bookkeeping ------------------------------------------------------------------
+def test_recycle_invariants_over_random_reranks():
+    rng = np.random.default_rng(23)
+    n, K = 64, 8
+    table = np.zeros(n, dtype=np.int32)
+    host = np.arange(100, 100 + n, dtype=np.int32)
+    free = list(range(1, K + 1))
+    owned = sorted(free)
+    old = np.empty(0, dtype=np.int32)
+    for it in range(20):
+        new = np.sort(rng.choice(n, size=K, replace=False)).astype(np.int32)
+        before = table.copy()
+        copies, free = oracle.recycle(old, new, table, host, free)
+        promoted = np.setdiff1d(new, old)
+        kept = np.intersect1d(new, old)
+        assert len(copies) == len(promoted)
+        np.testing.assert_array_equal(copies[:, 0], host[promoted])          # source = host block
+        np.testing.assert_array_equal(copies[:, 1], table[promoted])         # destination = new mapping
+        np.testing.assert_array_equal(table[kept], before[kept])             # kept pages do not move
+        resident = np.nonzero(table)[0]
+        np.testing.assert_array_equal(resident, new)                         # resident set == S_t
+        assert sorted(list(table[resident]) + free) == owned                 # blocks only permuted
+        assert len(set(table[resident])) == len(resident)
+        old = new
+    assert free == []
+
+
+def test_recycle_ordering_rule_and_cold_fill():
+    table = np.zeros(6, dtype=np.int32)
+    host = np.array([10, 11, 12, 13, 14, 15], dtype=np.int32)
+    copies, free = oracle.recycle([], [1, 4], table, host, [7, 9, 8])
+    assert copies.tolist() == [[11, 7], [14, 9]] and free == [8]
+    assert table.tolist() == [0, 7, 0, 0, 9, 0]
+    copies, free = oracle.recycle([1, 4], [0, 4, 5], table, host, free)   # evict 1, promote 0 and 5
+    assert copies.tolist() == [[10, 8], [15, 7]] and free == []
+    assert table.tolist() == [8, 0, 0, 0, 9, 7]
+    with pytest.raises(RuntimeError):
+        oracle.recycle([0, 4, 5], [0, 1, 2, 3], table.copy(), host, [])
+
+
+# ---- P8: the paper's printed numbers ------------------------------------------------------------
+def test_paper_topk_bytes():
+    g = GOLD["topk_kv_bytes"]
+    pages = g["budget_tokens"] // 16
+    page_bytes = 2 * 16 * g["head_dim"] * g["bytes_per_elem"]     # K and V of one 16-token page
+    assert g["stable_heads"] * pages * page_bytes == g["expected_mib"] * 2 ** 20
+
+
+def test_paper_memory_saving_curve():
+    g = GOLD["gpu_memory_saving"]
+    u, budget = g["unstable_fraction"], g["budget_tokens"]
+
+    def saving(length):
+        # resident pages per head counted with the oracle's own selection on arbitrary scores
+        n = -(-length // 16)
+        sel = oracle.select_topk(np.zeros(n), length, budget // 16)
+        return 1 - (u * n + (1 - u) * len(sel)) / n
+
+    assert abs(saving(g["length"]) - g["expected_about"]) < g["tolerance"]
+    assert saving(g["length"]) > 0.70
+    assert abs(saving(4_000_000) - g["asymptote"]) < 1e-3
+
+
+def test_paper_placement_example():
+    g = GOLD["placement_example"]
+    n, P = g["logical_pages"], 16
+    ctx = g["full_pages"] * P + 5
+    sel = oracle.select_topk(np.array([0.3, 0.9, 0.1, -5.0]), ctx, g["topk"])
+    assert len(sel) == g["stable_gpu_pages"] and (n - 1) in sel      # the partial page is a member
+    assert list(sel) == [1, 3]
+    assert g["host_pages"] == ctx // P and g["unstable_gpu_pages"] == n
+
+
+# ---- P9: schedule -------------------------------------------------------------------------------
+def _run_schedule(R, steps, K=None):
+    cfg = synth.make_config(1)
+    w = synth.Workload(cfg)
+    topk = [K] if K else list(cfg.topk)
+    dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, topk, R)
+    mm = oracle.seq_build_minmax(w.k[0], cfg.ctx[0])
+    hist, outs = [], []
+    for t in range(steps):
+        q = w.queries(t)
+        if t % R == 0:
+            dec.rerank(0, q[0], mm)
+        hist.append(dec.sel[(0, 0)].copy())
+        outs.append(dec.attend(0, q[0], w.k[0], w.v[0])[0])
+    return cfg, w, hist, outs
+
+
+def test_interval_one_reranks_every_step_and_long_interval_reuses_first_selection():
+    cfg, w, hist, _ = _run_schedule(1, 3)
+    mm = oracle.build_minmax(w.k[0][0], cfg.ctx[0])
+    for t in range(3):
+        s = oracle.page_scores(w.queries(t)[0, :cfg.group], mm)
+        np.testing.assert_array_equal(hist[t], oracle.select_topk(s, cfg.ctx[0], 8))
+    _, _, hist, _ = _run_schedule(100, 3)
+    assert all(np.array_equal(hist[0], h) for h in hist)
+
+
+def test_stable_head_with_full_budget_equals_dense():
+    cfg, w, hist, outs = _run_schedule(2, 2, K=128)
+    assert len(hist[0]) == 128
+    q = w.queries(1)[0]
+    for g in range(cfg.group):
+        ref, _ = dense_attention_numpy(q[g], w.k[0][0], w.v[0][0], cfg.ctx[0], 1 / np.sqrt(128))
+        np.testing.assert_allclose(outs[1][g], ref, rtol=1e-12, atol=1e-13)
+
+
+def test_sparse_attention_of_stable_head_is_close_to_dense_when_hot_pages_dominate():
+    """Sanity of the workload (not a pin): with planted hot pages, K = 8 of 128 pages keeps most of the
+    softmax mass, so the sparse output is near the dense one."""
+    cfg, w, hist, outs = _run_schedule(2, 1)
+    q = w.queries(0)[0]
+    ref, _ = dense_attention_numpy(q[0], w.k[0][0], w.v[0][0], cfg.ctx[0], 1 / np.sqrt(128))
+    assert np.abs(outs[0][0] - ref).max() < 0.5
