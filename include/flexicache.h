@@ -1,0 +1,210 @@
+/*
+ * flexicache.h -- C ABI of the MI355X (gfx950) decode hot path of FlexiCache (arXiv 2511.00868).
+ *
+ * One attention layer, one GPU.  Every KV head of every sequence has its own page set:
+ *   - unstable heads attend over all of their pages, which all live in HBM;
+ *   - stable heads attend over their top-K pages only, and only those live in HBM; the full copy
+ *     of a stable head lives in pinned host memory (Sec. 3.1, 3.3 of the paper).
+ * Every `rerank interval` steps the caller calls fc_rerank_topk (page scores from the MinMax cache,
+ * Sec. 3.2, then per-head top-K) and fc_promote_pages (set difference, physical block recycling,
+ * null block, host->HBM copies of the newly selected pages; Sec. 3.3, 3.4); every step it calls
+ * fc_sparse_decode_attn (split-KV decode attention restricted to each head's page set).
+ *
+ * Conventions
+ *   - "dev" pointers are device memory of `fc_config.device`; "host" pointers are ordinary host
+ *     memory read during the call; "pinned" pointers are page-locked host memory that the GPU can
+ *     address (hipHostMalloc / torch pin_memory).  The library never allocates or frees device or
+ *     pinned memory: all of it, including the workspace, is owned by the caller and must stay
+ *     valid until the work enqueued on it has finished.  The library owns two HIP events.
+ *   - Streams are hipStream_t passed as void*; NULL is the default stream.  All calls enqueue work
+ *     and return; only FC_PROMOTE_MEMCPY makes the host wait (for the small copy list).
+ *   - Every function returns FC_OK (0) or a negative fc_status; fc_last_error gives the text.
+ *     Argument errors are detected on the host before anything is launched.
+ *   - One host thread per fc_ctx at a time.
+ *   - bf16 = IEEE bfloat16 bit patterns (uint16_t).  head_dim D = 128, page_size P = 16 tokens,
+ *     group G = num_q_heads / num_kv_heads in {1, 2, 4, 8, 16}.
+ *
+ * Memory layouts fixed by this ABI (Nmax = max_pages_per_seq, Kmax = max_topk)
+ *   q            bf16 [batch][num_q_heads][D]; query head hq belongs to KV head hq / G
+ *   kv_pool      bf16 [num_blocks][2][2048]: one physical block = one page of one KV head = 8 KiB,
+ *                first the K half, token-major  K[token 0..15][dim 0..127],
+ *                then the V half, dim-major     V[dim 0..127][token 0..15]
+ *                (fc_write_kv_pages produces this layout; nothing else needs to know it).
+ *                Block 0 is the null block (Sec. 3.4 "Uniformity Through Null Block"): it is never
+ *                assigned to a page and its contents are never used.
+ *   host_pool    same block layout, in pinned host memory.
+ *   block_table  int32 [batch][num_kv_heads][Nmax]: logical page -> physical block, 0 = not in HBM
+ *   host_block_table  int32, same shape: logical page -> block of host_pool
+ *   minmax       bf16 [batch][num_kv_heads][Nmax][2][D]: row 0 per-dim minimum key of the page,
+ *                row 1 per-dim maximum (the MinMax cache of Sec. 3.2), over valid tokens only
+ *   topk_pages   int32 [batch][num_kv_heads][Kmax]: ascending logical page ids, -1 padded
+ *   topk_count   int32 [batch][num_kv_heads]
+ *   context_lens int32 [batch]: tokens in the sequence, >= 1; pages = ceil(len / 16) <= Nmax
+ *   stable_flag  uint8 [num_kv_heads] on the HOST: 1 = stable head (profiled offline, Sec. 2.3)
+ */
+#ifndef FLEXICACHE_H
+#define FLEXICACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fc_ctx fc_ctx;
+
+typedef enum {
+    FC_OK = 0,
+    FC_ERR_INVALID_ARG = -1,  /* null pointer, size out of range, inconsistent shapes */
+    FC_ERR_UNSUPPORTED = -2,  /* head_dim != 128, page_size != 16, unsupported group size */
+    FC_ERR_WORKSPACE = -3,    /* workspace or pinned scratch too small or misaligned */
+    FC_ERR_HIP = -4,          /* a HIP call failed; text in fc_last_error */
+    FC_ERR_STATE = -5         /* the device-side bookkeeping reported an inconsistency */
+} fc_status;
+
+typedef struct {
+    int32_t num_q_heads;
+    int32_t num_kv_heads;      /* <= 64 */
+    int32_t head_dim;          /* 128 */
+    int32_t page_size;         /* 16 */
+    int32_t max_batch;
+    int32_t max_pages_per_seq; /* Nmax */
+    int32_t max_topk;          /* Kmax */
+    float softmax_scale;       /* 0 -> 1/sqrt(head_dim) */
+    int32_t device;            /* HIP device ordinal */
+    int32_t attn_waves;        /* 0 -> chosen from the device (wavefronts the attention kernel runs) */
+} fc_config;
+
+/* Bytes of device workspace / pinned host scratch a context of this shape needs (0 on bad config). */
+size_t fc_workspace_bytes(const fc_config *cfg);
+size_t fc_host_scratch_bytes(const fc_config *cfg);
+
+/* Creates a context on cfg->device over caller-owned memory: `dev_workspace` (256-byte aligned,
+ * >= fc_workspace_bytes) and `pinned_scratch` (>= fc_host_scratch_bytes, GPU addressable).
+ * No device or pinned memory is allocated here or anywhere else in the library. */
+int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace, size_t workspace_bytes,
+              void *pinned_scratch, size_t scratch_bytes);
+int fc_destroy(fc_ctx *ctx);
+const char *fc_status_string(int status);
+const char *fc_last_error(const fc_ctx *ctx);
+
+/* ---- support: page writer and MinMax builder -------------------------------------------------- */
+
+/* Scatters token-major keys/values of one sequence into pool blocks in the kv_pool layout (the
+ * paged-cache write every paged-attention system has; Sec. 2 of the paper).
+ *   k_src, v_src  dev bf16 [num_kv_heads][tokens][D], tokens = n_pages * 16 (pad rows are copied
+ *                 as they are; consumers mask them by context length)
+ *   block_ids     dev int32 [num_kv_heads][ids_stride]: destination block of (head, page), pages
+ *                 0..n_pages-1; an id of 0 skips that page
+ *   pool          dev or pinned, `num_blocks` blocks. */
+int fc_write_kv_pages(fc_ctx *ctx, const void *k_src, const void *v_src, int32_t n_pages,
+                      const int32_t *block_ids, int32_t ids_stride, void *pool, int64_t num_blocks,
+                      void *stream);
+
+/* Builds MinMax rows (Sec. 3.2) of one sequence from pages resident in `pool`.
+ *   block_ids   dev int32 [num_kv_heads][ids_stride], as above (0 = skip)
+ *   page_list   dev int32 [n_list] logical pages to (re)build, or NULL for 0..n_pages-1 with
+ *               n_list = n_pages
+ *   context_len tokens in the sequence (host value): only valid tokens take part
+ *   minmax_seq  dev bf16 [num_kv_heads][Nmax][2][D] of this sequence. */
+int fc_build_minmax(fc_ctx *ctx, const void *pool, int64_t num_blocks, const int32_t *block_ids,
+                    int32_t ids_stride, const int32_t *page_list, int32_t n_list, int32_t context_len,
+                    void *minmax_seq, void *stream);
+
+/* ---- hot path ---------------------------------------------------------------------------------- */
+
+/* Page scoring + per-head top-K (Sec. 3.2; selection of Sec. 3.1).  For every sequence b with
+ * rerank_mask[b] != 0 and every stable head h:
+ *   score[p] = max over the G queries of the group of sum_i max(q_i * kmin[p][i], q_i * kmax[p][i])
+ *   (fp32 accumulation of exact bf16 products; the paper gives the per-query sum, the maximum over
+ *   the group is this library's reading), for p < ceil(context_len / 16);
+ *   selected = min(k_per_seq[b], pages) pages: the last page if it is partially filled (Sec. 3.3),
+ *   then the highest scores, ties to the lower page index; written ascending, -1 padded.
+ * Sequences with rerank_mask[b] == 0 and unstable heads keep their previous lists untouched. */
+typedef struct {
+    const void *q;               /* dev bf16 [batch][num_q_heads][D] */
+    const void *minmax;          /* dev bf16 [batch][num_kv_heads][Nmax][2][D] */
+    const int32_t *context_lens; /* dev [batch] */
+    const uint8_t *stable_flag;  /* host [num_kv_heads] */
+    const int32_t *k_per_seq;    /* dev [batch], 1 <= K_b <= Kmax */
+    const uint8_t *rerank_mask;  /* dev [batch] or NULL (= all sequences rerank) */
+    int32_t batch;               /* <= max_batch */
+    int32_t *topk_pages;         /* dev out [batch][num_kv_heads][Kmax] */
+    int32_t *topk_count;         /* dev out [batch][num_kv_heads] */
+    float *scores_out;           /* dev out [batch][num_kv_heads][Nmax] or NULL (workspace is used) */
+} fc_rerank_args;
+int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *args, void *stream);
+
+/* Promotion (Sec. 3.3 "Minimizing Transfer Size", Sec. 3.4 "Physical Block Reuse During Reranking"
+ * and "Uniformity Through Null Block").  For every reranking sequence and stable head:
+ *   evicted = resident \ new, promoted = new \ resident.  The head's available blocks are its free
+ *   list followed by the blocks of the evicted pages in ascending page order; promoted pages, in
+ *   ascending page order, take them from the front; the rest is the new free list.  Evicted entries
+ *   of block_table become 0, promoted entries get their block, resident_* becomes new_*.
+ *   Each promoted page is then copied host_pool[host_block_table[..]] -> kv_pool[block] on
+ *   `side_stream`, ordered after the bookkeeping kernel on `main_stream`; the next
+ *   fc_sparse_decode_attn on this context waits (on the GPU) for those copies.
+ * mode FC_PROMOTE_GATHER: one kernel on side_stream reads pinned host memory directly; the host
+ *   never waits.  mode FC_PROMOTE_MEMCPY: the host waits for the copy list, then issues one
+ *   hipMemcpyAsync per page on side_stream. */
+enum { FC_PROMOTE_GATHER = 0, FC_PROMOTE_MEMCPY = 1 };
+typedef struct {
+    const int32_t *new_pages;        /* dev [batch][num_kv_heads][Kmax] (S_t) */
+    const int32_t *new_count;        /* dev [batch][num_kv_heads] */
+    int32_t *resident_pages;         /* dev in/out: S_{t-1} on entry, S_t afterwards */
+    int32_t *resident_count;         /* dev in/out */
+    int32_t *block_table;            /* dev in/out [batch][num_kv_heads][Nmax] */
+    const int32_t *host_block_table; /* dev [batch][num_kv_heads][Nmax] */
+    int32_t *free_blocks;            /* dev in/out [batch][num_kv_heads][Kmax] */
+    int32_t *free_count;             /* dev in/out [batch][num_kv_heads] */
+    const uint8_t *stable_flag;      /* host [num_kv_heads] */
+    const uint8_t *rerank_mask;      /* dev [batch] or NULL */
+    void *kv_pool;                   /* dev */
+    int64_t num_pool_blocks;
+    const void *host_pool;           /* pinned */
+    int64_t num_host_blocks;
+    int32_t batch;
+    int32_t mode;                    /* FC_PROMOTE_GATHER | FC_PROMOTE_MEMCPY */
+    int32_t *promoted_count;         /* dev out [batch][num_kv_heads] or NULL (0 for heads not touched) */
+    int32_t *total_promoted;         /* pinned out (one int32) or NULL: pages copied by this call;
+                                        valid once side_stream has finished (at return for MEMCPY) */
+} fc_promote_args;
+int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream, void *side_stream);
+
+/* Head-heterogeneous paged decode attention (Sec. 3.1; split-KV decode attention as in Sec. 4.1).
+ * For every sequence b and KV head h the page set is topk_pages[b][h][0..topk_count) if the head is
+ * stable, all pages 0..ceil(context_len/16)-1 otherwise; each of the G query heads of the group gets
+ *   out = softmax(scale * q . K_set^T) V_set   over tokens < context_len, fp32,
+ *   lse = natural-log-sum-exp of the scaled logits (optional).
+ * Every page of the set must be resident (block_table entry != 0). */
+typedef struct {
+    const void *q;               /* dev bf16 [batch][num_q_heads][D] */
+    const void *kv_pool;         /* dev */
+    int64_t num_pool_blocks;
+    const int32_t *block_table;  /* dev [batch][num_kv_heads][Nmax] */
+    const int32_t *context_lens; /* dev [batch] */
+    const uint8_t *stable_flag;  /* host [num_kv_heads] */
+    const int32_t *topk_pages;   /* dev [batch][num_kv_heads][Kmax] */
+    const int32_t *topk_count;   /* dev [batch][num_kv_heads] */
+    int32_t batch;
+    float *out;                  /* dev out fp32 [batch][num_q_heads][D] */
+    float *lse;                  /* dev out fp32 [batch][num_q_heads] or NULL */
+} fc_attn_args;
+int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
+
+/* Reads (and clears) the device-side error word set by the bookkeeping kernels (a head owning too
+ * few blocks, an id out of range that was clamped).  Synchronises `stream`.  Returns FC_OK or
+ * FC_ERR_STATE. */
+int fc_check_device_state(fc_ctx *ctx, void *stream);
+
+/* Average duration in milliseconds of the dominant attention kernel (the split-KV partial kernel)
+ * between two calls, measured with HIP events on the stream it was launched on; used by
+ * benchmarks.  fc_profile_begin arms it, fc_profile_end synchronises and reports. */
+int fc_profile_begin(fc_ctx *ctx);
+int fc_profile_end(fc_ctx *ctx, double *avg_attn_kernel_ms, int32_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXICACHE_H */

@@ -1,0 +1,196 @@
+"""ctypes binding of libflexicache.so: argument marshalling only, one Python function per C entry
+point with the same name.  Tensors are torch tensors used as device / pinned memory; nothing is
+computed here.  There is no fallback: if the library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libflexicache.so")
+
+FC_OK, FC_ERR_INVALID_ARG, FC_ERR_UNSUPPORTED, FC_ERR_WORKSPACE, FC_ERR_HIP, FC_ERR_STATE = 0, -1, -2, -3, -4, -5
+FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY = 0, 1
+
+EXPORTS = ["fc_workspace_bytes", "fc_host_scratch_bytes", "fc_create", "fc_destroy", "fc_status_string",
+           "fc_last_error", "fc_write_kv_pages", "fc_build_minmax", "fc_rerank_topk", "fc_promote_pages",
+           "fc_sparse_decode_attn", "fc_check_device_state", "fc_profile_begin", "fc_profile_end"]
+
+
+class fc_config(C.Structure):
+    _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("page_size", C.c_int32), ("max_batch", C.c_int32), ("max_pages_per_seq", C.c_int32),
+                ("max_topk", C.c_int32), ("softmax_scale", C.c_float), ("device", C.c_int32),
+                ("attn_waves", C.c_int32)]
+
+
+class fc_rerank_args(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("minmax", C.c_void_p), ("context_lens", C.c_void_p),
+                ("stable_flag", C.c_void_p), ("k_per_seq", C.c_void_p), ("rerank_mask", C.c_void_p),
+                ("batch", C.c_int32), ("topk_pages", C.c_void_p), ("topk_count", C.c_void_p),
+                ("scores_out", C.c_void_p)]
+
+
+class fc_promote_args(C.Structure):
+    _fields_ = [("new_pages", C.c_void_p), ("new_count", C.c_void_p), ("resident_pages", C.c_void_p),
+                ("resident_count", C.c_void_p), ("block_table", C.c_void_p), ("host_block_table", C.c_void_p),
+                ("free_blocks", C.c_void_p), ("free_count", C.c_void_p), ("stable_flag", C.c_void_p),
+                ("rerank_mask", C.c_void_p), ("kv_pool", C.c_void_p), ("num_pool_blocks", C.c_int64),
+                ("host_pool", C.c_void_p), ("num_host_blocks", C.c_int64), ("batch", C.c_int32),
+                ("mode", C.c_int32), ("promoted_count", C.c_void_p), ("total_promoted", C.c_void_p)]
+
+
+class fc_attn_args(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("kv_pool", C.c_void_p), ("num_pool_blocks", C.c_int64),
+                ("block_table", C.c_void_p), ("context_lens", C.c_void_p), ("stable_flag", C.c_void_p),
+                ("topk_pages", C.c_void_p), ("topk_count", C.c_void_p), ("batch", C.c_int32),
+                ("out", C.c_void_p), ("lse", C.c_void_p)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Loads the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_00868_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        L.fc_workspace_bytes.argtypes = [C.POINTER(fc_config)]
+        L.fc_workspace_bytes.restype = C.c_size_t
+        L.fc_host_scratch_bytes.argtypes = [C.POINTER(fc_config)]
+        L.fc_host_scratch_bytes.restype = C.c_size_t
+        L.fc_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(fc_config), C.c_void_p, C.c_size_t,
+                                C.c_void_p, C.c_size_t]
+        L.fc_destroy.argtypes = [C.c_void_p]
+        L.fc_status_string.argtypes = [C.c_int]
+        L.fc_status_string.restype = C.c_char_p
+        L.fc_last_error.argtypes = [C.c_void_p]
+        L.fc_last_error.restype = C.c_char_p
+        L.fc_write_kv_pages.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_int64, C.c_void_p]
+        L.fc_build_minmax.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.fc_rerank_topk.argtypes = [C.c_void_p, C.POINTER(fc_rerank_args), C.c_void_p]
+        L.fc_promote_pages.argtypes = [C.c_void_p, C.POINTER(fc_promote_args), C.c_void_p, C.c_void_p]
+        L.fc_sparse_decode_attn.argtypes = [C.c_void_p, C.POINTER(fc_attn_args), C.c_void_p]
+        L.fc_check_device_state.argtypes = [C.c_void_p, C.c_void_p]
+        L.fc_profile_begin.argtypes = [C.c_void_p]
+        L.fc_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        _lib = L
+    return _lib
+
+
+class FlexiCacheError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"flexicache: {text} (status {status})")
+        self.status = status
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _host_u8(flags):
+    arr = (C.c_uint8 * len(flags))(*[1 if f else 0 for f in flags])
+    return arr
+
+
+class Context:
+    """Owns the caller-side memory an fc_ctx needs (device workspace, pinned scratch) and exposes the
+    C entry points under their own names."""
+
+    def __init__(self, *, num_q_heads: int, num_kv_heads: int, max_batch: int, max_pages_per_seq: int,
+                 max_topk: int, softmax_scale: float = 0.0, device: int = 0, attn_waves: int = 0,
+                 head_dim: int = 128, page_size: int = 16):
+        import torch
+        self.torch = torch
+        self.lib = load()
+        self.cfg = fc_config(num_q_heads, num_kv_heads, head_dim, page_size, max_batch, max_pages_per_seq,
+                             max_topk, softmax_scale, device, attn_waves)
+        ws = self.lib.fc_workspace_bytes(C.byref(self.cfg))
+        hs = self.lib.fc_host_scratch_bytes(C.byref(self.cfg))
+        if ws == 0 or hs == 0:
+            raise FlexiCacheError(FC_ERR_INVALID_ARG, "configuration rejected")
+        if not torch.cuda.is_available():
+            raise RuntimeError("flexicache needs a GPU: no HIP device is visible (there is no CPU fallback)")
+        self.device = torch.device("cuda", device)
+        self.workspace = torch.zeros(ws, dtype=torch.uint8, device=self.device)
+        self.scratch = torch.zeros(hs, dtype=torch.uint8, pin_memory=True)
+        self.handle = C.c_void_p()
+        st = self.lib.fc_create(C.byref(self.handle), C.byref(self.cfg), self.workspace.data_ptr(), ws,
+                                self.scratch.data_ptr(), hs)
+        if st != FC_OK:
+            raise FlexiCacheError(st, self.lib.fc_status_string(st).decode())
+
+    def close(self):
+        if getattr(self, "handle", None) and self.handle.value:
+            self.torch.cuda.synchronize(self.device)
+            self.lib.fc_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != FC_OK:
+            raise FlexiCacheError(st, self.lib.fc_last_error(self.handle).decode() or
+                                  self.lib.fc_status_string(st).decode())
+
+    @staticmethod
+    def _stream(stream) -> Optional[int]:
+        return None if stream is None else stream.cuda_stream
+
+    # ---- entry points, same names as the C ABI ---------------------------------------------------
+    def fc_write_kv_pages(self, k_src, v_src, n_pages: int, block_ids, pool, num_blocks: int, stream=None):
+        self._check(self.lib.fc_write_kv_pages(self.handle, _ptr(k_src), _ptr(v_src), n_pages, _ptr(block_ids),
+                                               block_ids.stride(0), _ptr(pool), num_blocks, self._stream(stream)))
+
+    def fc_build_minmax(self, pool, num_blocks: int, block_ids, page_list, n_list: int, context_len: int,
+                        minmax_seq, stream=None):
+        self._check(self.lib.fc_build_minmax(self.handle, _ptr(pool), num_blocks, _ptr(block_ids),
+                                             block_ids.stride(0), _ptr(page_list), n_list, context_len,
+                                             _ptr(minmax_seq), self._stream(stream)))
+
+    def fc_rerank_topk(self, *, q, minmax, context_lens, stable_flag, k_per_seq, batch: int, topk_pages,
+                       topk_count, rerank_mask=None, scores_out=None, stream=None):
+        flags = _host_u8(stable_flag)
+        a = fc_rerank_args(_ptr(q), _ptr(minmax), _ptr(context_lens), C.addressof(flags), _ptr(k_per_seq),
+                           _ptr(rerank_mask), batch, _ptr(topk_pages), _ptr(topk_count), _ptr(scores_out))
+        self._check(self.lib.fc_rerank_topk(self.handle, C.byref(a), self._stream(stream)))
+
+    def fc_promote_pages(self, *, new_pages, new_count, resident_pages, resident_count, block_table,
+                         host_block_table, free_blocks, free_count, stable_flag, kv_pool, num_pool_blocks: int,
+                         host_pool, num_host_blocks: int, batch: int, main_stream, side_stream,
+                         mode: int = FC_PROMOTE_GATHER, rerank_mask=None, promoted_count=None, total_promoted=None):
+        flags = _host_u8(stable_flag)
+        a = fc_promote_args(_ptr(new_pages), _ptr(new_count), _ptr(resident_pages), _ptr(resident_count),
+                            _ptr(block_table), _ptr(host_block_table), _ptr(free_blocks), _ptr(free_count),
+                            C.addressof(flags), _ptr(rerank_mask), _ptr(kv_pool), num_pool_blocks, _ptr(host_pool),
+                            num_host_blocks, batch, mode, _ptr(promoted_count), _ptr(total_promoted))
+        self._check(self.lib.fc_promote_pages(self.handle, C.byref(a), self._stream(main_stream),
+                                              self._stream(side_stream)))
+
+    def fc_sparse_decode_attn(self, *, q, kv_pool, num_pool_blocks: int, block_table, context_lens, stable_flag,
+                              topk_pages, topk_count, batch: int, out, lse=None, stream=None):
+        flags = _host_u8(stable_flag)
+        a = fc_attn_args(_ptr(q), _ptr(kv_pool), num_pool_blocks, _ptr(block_table), _ptr(context_lens),
+                         C.addressof(flags), _ptr(topk_pages), _ptr(topk_count), batch, _ptr(out), _ptr(lse))
+        self._check(self.lib.fc_sparse_decode_attn(self.handle, C.byref(a), self._stream(stream)))
+
+    def fc_check_device_state(self, stream=None):
+        self._check(self.lib.fc_check_device_state(self.handle, self._stream(stream)))
+
+    def fc_profile_begin(self):
+        self._check(self.lib.fc_profile_begin(self.handle))
+
+    def fc_profile_end(self):
+        ms, n = C.c_double(), C.c_int32()
+        self._check(self.lib.fc_profile_end(self.handle, C.byref(ms), C.byref(n)))
+        return ms.value, n.value

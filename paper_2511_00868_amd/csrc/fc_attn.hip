@@ -1,0 +1,364 @@
+// fc_sparse_decode_attn: head-heterogeneous paged decode attention (Sec. 3.1 of the paper; the
+// split-KV + merge structure of decode attention named in Sec. 4.1).
+//
+// Three kernels per call:
+//   plan     one workgroup: page count of every (sequence, KV head) item -- all pages for an unstable
+//            head, the top-K count for a stable one -- prefix sums over items, the number of pages
+//            each wavefront takes (total / wavefronts, rounded up) and each wavefront's first item.
+//   partial  every wavefront streams its equal share of the concatenated page lists, independent of
+//            item boundaries, so a 2048-page unstable head and a 204-page stable head cost the
+//            same per page and no wavefront is left with a long tail.  Per page: QK^T and PV on
+//            the matrix cores, online softmax in registers.  One partial (m, l, acc) per
+//            (wavefront, item) pair it touches.
+//   merge    one workgroup per item: log-sum-exp combination of that item's partials.
+//
+// Matrix-core mapping (wave64, 16x16 tiles; lane = 16*j + n):
+//   S^T[key][query] = K_page[16 x 128] . Q^T[128 x 16]   4 x v_mfma_f32_16x16x32_bf16
+//       A = K rows straight from the page (lane reads 16 B of key row n, dims 32s+8j..+8),
+//       B = Q^T, the G real query heads in columns 0..G-1, zero columns after them.
+//       The result leaves lane (n, j) holding keys 4j..4j+3 of query n ...
+//   O^T[dim][query] += V^T[16 dims x 16 keys] . P^T[16 keys x 16 queries]   8 x v_mfma_f32_16x16x16_bf16
+//       ... which is exactly the B-operand layout of the 16x16x16 shape, so the probabilities never
+//       move between lanes.  A = the dim-major V half of the page (lane reads 8 B: dim 16c+n,
+//       keys 4j..4j+3).  P is split into a high and a low bf16 part (two MFMAs) so that PV keeps
+//       ~16 mantissa bits; a single bf16 P would by itself cost 2^-9 relative error.
+#include "fc_internal.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
+
+constexpr int FC_ATTN_NBUF = 3;            // pages in flight per wavefront
+constexpr int FC_MIN_PAGES_PER_WAVE = 2;
+
+struct fc_attn_params {
+    const uint16_t *q;
+    const char *pool;
+    long long num_blocks;
+    const int32_t *block_table;
+    const int32_t *context_lens;
+    const int32_t *topk_pages;
+    const int32_t *topk_count;
+    unsigned long long stable_mask;
+    int batch, Hq, Hkv, G, Nmax, Kmax;
+    int n_waves;
+    float scale_log2;
+    int32_t *seg_start;
+    int32_t *plan_meta;
+    int32_t *wave_item;
+    float *part_ml;
+    float *part_acc;
+    float *out;
+    float *lse;
+};
+
+__device__ __forceinline__ int fc_pages_of(int ctx, int Nmax)
+{
+    int n = (ctx + FC_P - 1) / FC_P;
+    return n < 0 ? 0 : (n > Nmax ? Nmax : n);
+}
+
+// ---- plan ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void fc_attn_plan_kernel(fc_attn_params p)
+{
+    __shared__ int wave_tot[16];
+    __shared__ int carry;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int items = p.batch * p.Hkv;
+    if (tid == 0) { carry = 0; p.seg_start[0] = 0; }
+    __syncthreads();
+    for (int base = 0; base < items; base += 1024) {
+        const int i = base + tid;
+        int cnt = 0;
+        if (i < items) {
+            const int b = i / p.Hkv, h = i - b * p.Hkv;
+            const int n = fc_pages_of(p.context_lens[b], p.Nmax);
+            if ((p.stable_mask >> h) & 1ull) {
+                int k = p.topk_count[i];
+                cnt = k < 0 ? 0 : (k > n ? n : k);
+                if (cnt > p.Kmax) cnt = p.Kmax;
+            } else {
+                cnt = n;
+            }
+        }
+        int x = cnt;   // inclusive scan inside the wavefront
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            int y = __shfl_up(x, d);
+            if (lane >= d) x += y;
+        }
+        if (lane == 63) wave_tot[wv] = x;
+        __syncthreads();
+        int off = carry;
+        for (int k = 0; k < wv; ++k) off += wave_tot[k];
+        if (i < items) p.seg_start[i + 1] = off + x;
+        __syncthreads();
+        if (tid == 1023) carry = off + x;
+        __syncthreads();
+    }
+    const int total = carry;
+    int L = (total + p.n_waves - 1) / p.n_waves;
+    if (L < FC_MIN_PAGES_PER_WAVE) L = FC_MIN_PAGES_PER_WAVE;
+    if (tid == 0) { p.plan_meta[0] = total; p.plan_meta[1] = L; }
+    __threadfence_block();
+    __syncthreads();
+    for (int w = tid; w < p.n_waves; w += 1024) {
+        const long long start = (long long)w * L;
+        int it = -1;
+        if (start < total) {   // last item whose first page is <= start and that is not empty
+            int lo = 0, hi = items;            // find the item with seg_start[it] <= start < seg_start[it+1]
+            while (hi - lo > 1) {
+                int mid = (lo + hi) >> 1;
+                if (p.seg_start[mid] <= start) lo = mid; else hi = mid;
+            }
+            it = lo;
+        }
+        p.wave_item[w] = it;
+    }
+}
+
+// ---- partial ---------------------------------------------------------------------------------------
+struct fc_page_regs {
+    bf16x8_t k[4];
+    short4_t v[8];
+};
+
+__device__ __forceinline__ void fc_load_page(fc_page_regs &r, const char *pool, int blk, int lane_k_off, int lane_v_off)
+{
+    const char *base = pool + (size_t)blk * FC_PAGE_BYTES;
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+        r.k[s] = *reinterpret_cast<const bf16x8_t *>(base + lane_k_off + s * 64);
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+        r.v[c] = *reinterpret_cast<const short4_t *>(base + FC_HALF_BYTES + lane_v_off + c * 512);
+}
+
+struct fc_softmax_state {
+    float m;          // running maximum of the scaled logits, log2 units, common to the 4 lanes of a query
+    float l;          // this lane's share of the running denominator
+    float4_t acc[8];  // O^T[dim 16c + 4j + v][query n]
+};
+
+__device__ __forceinline__ void fc_consume_page(fc_softmax_state &st, fc_page_regs &r, const bf16x8_t (&qb)[4],
+                                                int ntok, int j, float scale_log2)
+{
+    float4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(r.k[i], qb[i], s, 0, 0, 0);
+
+    float z[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) z[v] = (4 * j + v < ntok) ? s[v] * scale_log2 : -INFINITY;
+    if (ntok < FC_P) {   // partial page: pad tokens may hold anything, and 0 * NaN would poison PV
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * j + e >= ntok) r.v[c][e] = 0;
+    }
+    float mloc = fmaxf(fmaxf(z[0], z[1]), fmaxf(z[2], z[3]));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+    const float m_new = fmaxf(st.m, mloc);
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    float pr[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) pr[v] = __builtin_amdgcn_exp2f(z[v] - m_new);
+    st.l = st.l * alpha + ((pr[0] + pr[1]) + (pr[2] + pr[3]));
+    st.m = m_new;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) st.acc[c] *= alpha;
+    }
+    // P = hi + lo, both bf16 (truncation: hi keeps the top 8 mantissa bits, lo the next 8)
+    short4_t ph, pl;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const uint32_t u = __float_as_uint(pr[v]);
+        const float hi = __uint_as_float(u & 0xFFFF0000u);
+        ph[v] = (short)(u >> 16);
+        pl[v] = (short)(__float_as_uint(pr[v] - hi) >> 16);
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        st.acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(r.v[c], ph, st.acc[c], 0, 0, 0);
+        st.acc[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(r.v[c], pl, st.acc[c], 0, 0, 0);
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void fc_attn_partial_kernel(fc_attn_params p)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int item = p.wave_item[w];
+    if (item < 0) return;
+    const int total = p.plan_meta[0], L = p.plan_meta[1];
+    int g0 = w * L;
+    const int g1 = min(g0 + L, total);
+    const int n = lane & 15, j = lane >> 4;
+    const int lane_k_off = n * 256 + j * 16;
+    const int lane_v_off = n * 32 + j * 8;
+    const int items = p.batch * p.Hkv;
+
+    while (g0 < g1 && item < items) {
+        const int s0 = p.seg_start[item], s1 = p.seg_start[item + 1];
+        if (s1 <= g0) { ++item; continue; }             // empty item
+        const int lo = g0 - s0, hi = min(g1, s1) - s0;
+        const int b = item / p.Hkv, h = item - b * p.Hkv;
+        const bool stable = (p.stable_mask >> h) & 1ull;
+        const int ctx = p.context_lens[b];
+        const int n_pages = fc_pages_of(ctx, p.Nmax);
+        const int last_page = n_pages - 1;
+        const int last_ntok = min(FC_P, ctx - last_page * FC_P);
+
+        bf16x8_t qb[4];
+        {
+            const uint16_t *qrow = p.q + ((size_t)b * p.Hq + (size_t)h * p.G + (n < p.G ? n : 0)) * FC_D;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                bf16x8_t x = *reinterpret_cast<const bf16x8_t *>(qrow + 32 * s + 8 * j);
+                if (n >= p.G) x = bf16x8_t{0, 0, 0, 0, 0, 0, 0, 0};
+                qb[s] = x;
+            }
+        }
+        fc_softmax_state st;
+        st.m = -INFINITY;
+        st.l = 0.f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) st.acc[c] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+        const int32_t *tbl = p.block_table + (size_t)item * p.Nmax;
+        const int32_t *lst = p.topk_pages + (size_t)item * p.Kmax;
+        for (int base = lo; base < hi; base += 64) {
+            const int cnt = min(64, hi - base);
+            int blk_v = 0, ntok_v = FC_P;
+            if (lane < cnt) {
+                int logical = stable ? lst[base + lane] : base + lane;
+                logical = logical < 0 ? 0 : (logical > last_page ? last_page : logical);
+                long long blk = tbl[logical];
+                blk = blk < 0 ? 0 : (blk >= p.num_blocks ? p.num_blocks - 1 : blk);
+                blk_v = (int)blk;
+                ntok_v = logical == last_page ? last_ntok : FC_P;
+            }
+            fc_page_regs buf[FC_ATTN_NBUF];
+#pragma unroll
+            for (int i = 0; i < FC_ATTN_NBUF; ++i)
+                if (i < cnt) fc_load_page(buf[i], p.pool, __builtin_amdgcn_readlane(blk_v, i), lane_k_off, lane_v_off);
+            for (int t0 = 0; t0 < cnt; t0 += FC_ATTN_NBUF) {
+#pragma unroll
+                for (int i = 0; i < FC_ATTN_NBUF; ++i) {
+                    const int t = t0 + i;
+                    if (t < cnt) {
+                        const int ntok = __builtin_amdgcn_readlane(ntok_v, t);
+                        fc_consume_page(st, buf[i], qb, ntok, j, p.scale_log2);
+                        if (t + FC_ATTN_NBUF < cnt)
+                            fc_load_page(buf[i], p.pool, __builtin_amdgcn_readlane(blk_v, t + FC_ATTN_NBUF),
+                                         lane_k_off, lane_v_off);
+                    }
+                }
+            }
+        }
+        float l = st.l;
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        const int slot = w + item;
+        if (n < p.G) {
+            if (j == 0) {
+                p.part_ml[((size_t)slot * 16 + n) * 2 + 0] = st.m;
+                p.part_ml[((size_t)slot * 16 + n) * 2 + 1] = l;
+            }
+            float *dst = p.part_acc + ((size_t)slot * p.G + n) * FC_D + 4 * j;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) *reinterpret_cast<float4_t *>(dst + 16 * c) = st.acc[c];
+        }
+        g0 = s0 + hi;
+        ++item;
+    }
+}
+
+// ---- merge -----------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
+{
+    const int item = blockIdx.x;
+    const int b = item / p.Hkv, h = item - b * p.Hkv;
+    const int s0 = p.seg_start[item], s1 = p.seg_start[item + 1];
+    const int L = p.plan_meta[1];
+    const int w_first = s0 / L, w_last = s1 > s0 ? (s1 - 1) / L : w_first - 1;
+    for (int o = threadIdx.x; o < p.G * (FC_D / 4); o += blockDim.x) {
+        const int g = o / (FC_D / 4), d4 = o - g * (FC_D / 4);
+        float mstar = -INFINITY;
+        for (int w = w_first; w <= w_last; ++w)
+            mstar = fmaxf(mstar, p.part_ml[((size_t)(w + item) * 16 + g) * 2]);
+        float lsum = 0.f;
+        float4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+        for (int w = w_first; w <= w_last; ++w) {
+            const size_t slot = (size_t)(w + item);
+            const float wt = __builtin_amdgcn_exp2f(p.part_ml[(slot * 16 + g) * 2] - mstar);
+            lsum += wt * p.part_ml[(slot * 16 + g) * 2 + 1];
+            const float4_t a = *reinterpret_cast<const float4_t *>(p.part_acc + (slot * p.G + g) * FC_D + 4 * d4);
+            acc += wt * a;
+        }
+        const size_t row = (size_t)b * p.Hq + (size_t)h * p.G + g;
+        float4_t r = {0.f, 0.f, 0.f, 0.f};
+        if (w_last >= w_first) r = acc * (1.0f / lsum);
+        *reinterpret_cast<float4_t *>(p.out + row * FC_D + 4 * d4) = r;
+        if (p.lse && d4 == 0)
+            p.lse[row] = w_last >= w_first ? (mstar + __builtin_amdgcn_logf(lsum)) * 0.6931471805599453f : -INFINITY;
+    }
+}
+
+extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    FC_REQUIRE(ctx, a, "fc_sparse_decode_attn: args is NULL");
+    FC_REQUIRE(ctx, a->q && a->kv_pool && a->block_table && a->context_lens && a->stable_flag && a->out,
+               "fc_sparse_decode_attn: NULL pointer among q, kv_pool, block_table, context_lens, stable_flag, out");
+    FC_REQUIRE(ctx, a->batch >= 1 && a->batch <= ctx->cfg.max_batch, "fc_sparse_decode_attn: batch=%d outside 1..%d", a->batch, ctx->cfg.max_batch);
+    FC_REQUIRE(ctx, a->num_pool_blocks >= 2, "fc_sparse_decode_attn: num_pool_blocks must be >= 2");
+    const uint64_t mask = fc_stable_mask(ctx->cfg, a->stable_flag);
+    FC_REQUIRE(ctx, mask == 0 || (a->topk_pages && a->topk_count), "fc_sparse_decode_attn: stable heads need topk_pages and topk_count");
+    hipStream_t s = (hipStream_t)stream;
+
+    fc_attn_params p;
+    p.q = (const uint16_t *)a->q;
+    p.pool = (const char *)a->kv_pool;
+    p.num_blocks = a->num_pool_blocks;
+    p.block_table = a->block_table;
+    p.context_lens = a->context_lens;
+    p.topk_pages = a->topk_pages ? a->topk_pages : a->block_table;   // never read when mask == 0
+    p.topk_count = a->topk_count ? a->topk_count : a->context_lens;
+    p.stable_mask = mask;
+    p.batch = a->batch;
+    p.Hq = ctx->cfg.num_q_heads;
+    p.Hkv = ctx->cfg.num_kv_heads;
+    p.G = ctx->G;
+    p.Nmax = ctx->cfg.max_pages_per_seq;
+    p.Kmax = ctx->cfg.max_topk;
+    p.n_waves = ctx->attn_waves;
+    p.scale_log2 = ctx->scale_log2;
+    p.seg_start = fc_ws_ptr<int32_t>(ctx, ctx->lay.seg_start);
+    p.plan_meta = fc_ws_ptr<int32_t>(ctx, ctx->lay.plan_meta);
+    p.wave_item = fc_ws_ptr<int32_t>(ctx, ctx->lay.wave_item);
+    p.part_ml = fc_ws_ptr<float>(ctx, ctx->lay.part_ml);
+    p.part_acc = fc_ws_ptr<float>(ctx, ctx->lay.part_acc);
+    p.out = a->out;
+    p.lse = a->lse;
+
+    if (ctx->copies_pending) {   // promoted pages still in flight on the side stream
+        FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_copies_done, 0));
+        ctx->copies_pending = false;
+    }
+    hipLaunchKernelGGL(fc_attn_plan_kernel, dim3(1), dim3(1024), 0, s, p);
+    const bool prof = ctx->profiling && ctx->prof_used < FC_MAX_PROFILE_EVENTS;
+    if (prof) FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used], s));
+    hipLaunchKernelGGL(fc_attn_partial_kernel, dim3(p.n_waves / 4), dim3(256), 0, s, p);
+    if (prof) {
+        FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used + 1], s));
+        ++ctx->prof_used;
+    }
+    hipLaunchKernelGGL(fc_attn_merge_kernel, dim3(p.batch * p.Hkv), dim3(256), 0, s, p);
+    FC_HIP(ctx, hipGetLastError());
+    return FC_OK;
+}

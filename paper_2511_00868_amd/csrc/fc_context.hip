@@ -1,0 +1,220 @@
+// Context life cycle, argument checking helpers, workspace partition, error text, kernel timing.
+#include <math.h>
+#include <stdarg.h>
+#include <stdlib.h>
+
+#include "fc_internal.h"
+
+static int fc_check_config(const fc_config *c, const char **why)
+{
+    *why = nullptr;
+    if (!c) { *why = "config is NULL"; return FC_ERR_INVALID_ARG; }
+    if (c->head_dim != FC_D) { *why = "head_dim must be 128"; return FC_ERR_UNSUPPORTED; }
+    if (c->page_size != FC_P) { *why = "page_size must be 16"; return FC_ERR_UNSUPPORTED; }
+    if (c->num_kv_heads < 1 || c->num_kv_heads > 64) { *why = "num_kv_heads must be in 1..64"; return FC_ERR_INVALID_ARG; }
+    if (c->num_q_heads < c->num_kv_heads || c->num_q_heads % c->num_kv_heads != 0) {
+        *why = "num_q_heads must be a multiple of num_kv_heads"; return FC_ERR_INVALID_ARG;
+    }
+    int G = c->num_q_heads / c->num_kv_heads;
+    if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) { *why = "group size must be 1, 2, 4, 8 or 16"; return FC_ERR_UNSUPPORTED; }
+    if (c->max_batch < 1 || c->max_batch > (1 << 16)) { *why = "max_batch out of range"; return FC_ERR_INVALID_ARG; }
+    if (c->max_pages_per_seq < 1 || c->max_pages_per_seq > (1 << 20)) { *why = "max_pages_per_seq out of range"; return FC_ERR_INVALID_ARG; }
+    if (c->max_topk < 1 || c->max_topk > c->max_pages_per_seq) { *why = "max_topk must be in 1..max_pages_per_seq"; return FC_ERR_INVALID_ARG; }
+    if (!(c->softmax_scale >= 0.0f) || !isfinite(c->softmax_scale)) { *why = "softmax_scale must be finite and >= 0"; return FC_ERR_INVALID_ARG; }
+    if (c->attn_waves < 0 || c->attn_waves > (1 << 16)) { *why = "attn_waves out of range"; return FC_ERR_INVALID_ARG; }
+    if (c->device < 0) { *why = "device must be >= 0"; return FC_ERR_INVALID_ARG; }
+    return FC_OK;
+}
+
+// Wavefronts of the attention kernel when the caller does not choose: a multiple of 4 (one
+// workgroup = 4 wavefronts).  2048 = 256 CUs x 8 on MI355X; used for sizing when no device is asked.
+static int fc_default_waves(int num_cus) { return (num_cus > 0 ? num_cus : 256) * 8; }
+
+static void fc_make_layout(const fc_config &c, int attn_waves, fc_ws_layout *l)
+{
+    const size_t items = (size_t)c.max_batch * c.num_kv_heads;
+    const int G = c.num_q_heads / c.num_kv_heads;
+    const size_t slots = (size_t)attn_waves + items;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = fc_align_up(off + bytes, 256); return o; };
+    l->scores = take(items * (size_t)c.max_pages_per_seq * sizeof(float));
+    l->seg_start = take((items + 1) * sizeof(int32_t));
+    l->plan_meta = take(8 * sizeof(int32_t));
+    l->wave_item = take((size_t)attn_waves * sizeof(int32_t));
+    l->part_ml = take(slots * 16 * 2 * sizeof(float));
+    l->part_acc = take(slots * (size_t)G * FC_D * sizeof(float));
+    l->copy_list = take(items * (size_t)c.max_topk * 2 * sizeof(int32_t));
+    l->counters = take(8 * sizeof(int32_t));
+    l->total = off;
+}
+
+static int fc_resolve_waves(const fc_config *cfg, int num_cus)
+{
+    int w = cfg->attn_waves > 0 ? cfg->attn_waves : fc_default_waves(num_cus);
+    const char *env = getenv("FC_ATTN_WAVES");
+    if (cfg->attn_waves == 0 && env && atoi(env) > 0) w = atoi(env);
+    w = (w + 3) / 4 * 4;
+    return w;
+}
+
+extern "C" size_t fc_workspace_bytes(const fc_config *cfg)
+{
+    const char *why;
+    if (fc_check_config(cfg, &why) != FC_OK) return 0;
+    // Sized for the larger of the default and the requested wave count so that it does not depend
+    // on the device the context is later created on (up to 512 CUs).
+    int waves = fc_resolve_waves(cfg, 512);
+    fc_ws_layout l;
+    fc_make_layout(*cfg, waves, &l);
+    return l.total;
+}
+
+extern "C" size_t fc_host_scratch_bytes(const fc_config *cfg)
+{
+    const char *why;
+    if (fc_check_config(cfg, &why) != FC_OK) return 0;
+    const size_t items = (size_t)cfg->max_batch * cfg->num_kv_heads;
+    return 256 + items * (size_t)cfg->max_topk * 2 * sizeof(int32_t);
+}
+
+int fc_fail(fc_ctx *ctx, int status, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof ctx->err, fmt, ap);
+        va_end(ap);
+    }
+    return status;
+}
+
+int fc_hip_fail(fc_ctx *ctx, hipError_t e, const char *what)
+{
+    return fc_fail(ctx, FC_ERR_HIP, "%s failed: %s", what, hipGetErrorString(e));
+}
+
+uint64_t fc_stable_mask(const fc_config &cfg, const uint8_t *stable_flag)
+{
+    uint64_t m = 0;
+    for (int h = 0; h < cfg.num_kv_heads; ++h)
+        if (stable_flag[h]) m |= (uint64_t)1 << h;
+    return m;
+}
+
+extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace, size_t workspace_bytes,
+                         void *pinned_scratch, size_t scratch_bytes)
+{
+    if (!out) return FC_ERR_INVALID_ARG;
+    *out = nullptr;
+    const char *why;
+    int st = fc_check_config(cfg, &why);
+    if (st != FC_OK) return st;
+    if (!dev_workspace || !pinned_scratch) return FC_ERR_INVALID_ARG;
+    if (((uintptr_t)dev_workspace & 255) != 0) return FC_ERR_WORKSPACE;
+    if (workspace_bytes < fc_workspace_bytes(cfg) || scratch_bytes < fc_host_scratch_bytes(cfg))
+        return FC_ERR_WORKSPACE;
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return FC_ERR_HIP;   // no GPU: fail loudly
+    if (cfg->device >= ndev) return FC_ERR_INVALID_ARG;
+    if (hipSetDevice(cfg->device) != hipSuccess) return FC_ERR_HIP;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) return FC_ERR_HIP;
+
+    fc_ctx *c = new fc_ctx();
+    memset(c, 0, sizeof *c);
+    c->cfg = *cfg;
+    c->G = cfg->num_q_heads / cfg->num_kv_heads;
+    c->max_items = cfg->max_batch * cfg->num_kv_heads;
+    c->num_cus = prop.multiProcessorCount;
+    c->attn_waves = fc_resolve_waves(cfg, c->num_cus);
+    c->slots = c->attn_waves + c->max_items;
+    float scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / sqrtf((float)FC_D);
+    c->cfg.softmax_scale = scale;
+    c->scale_log2 = scale * 1.4426950408889634f;
+    c->ws = (char *)dev_workspace;
+    c->ws_bytes = workspace_bytes;
+    c->scratch = (char *)pinned_scratch;
+    c->scratch_bytes = scratch_bytes;
+    fc_make_layout(c->cfg, c->attn_waves, &c->lay);
+    if (c->lay.total > workspace_bytes) { delete c; return FC_ERR_WORKSPACE; }
+    if (hipEventCreateWithFlags(&c->ev_diff_done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_copies_done, hipEventDisableTiming) != hipSuccess) {
+        delete c;
+        return FC_ERR_HIP;
+    }
+    c->copies_pending = false;
+    c->err[0] = 0;
+    *out = c;
+    return FC_OK;
+}
+
+extern "C" int fc_destroy(fc_ctx *ctx)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    hipEventDestroy(ctx->ev_diff_done);
+    hipEventDestroy(ctx->ev_copies_done);
+    for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
+        if (ctx->prof_ev[i]) hipEventDestroy(ctx->prof_ev[i]);
+    delete ctx;
+    return FC_OK;
+}
+
+extern "C" const char *fc_status_string(int status)
+{
+    switch (status) {
+    case FC_OK: return "ok";
+    case FC_ERR_INVALID_ARG: return "invalid argument";
+    case FC_ERR_UNSUPPORTED: return "unsupported shape";
+    case FC_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case FC_ERR_HIP: return "HIP call failed";
+    case FC_ERR_STATE: return "device-side bookkeeping inconsistency";
+    default: return "unknown status";
+    }
+}
+
+extern "C" const char *fc_last_error(const fc_ctx *ctx) { return ctx ? ctx->err : "context is NULL"; }
+
+extern "C" int fc_check_device_state(fc_ctx *ctx, void *stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    int32_t *dev_err = fc_ws_ptr<int32_t>(ctx, ctx->lay.counters) + 1;
+    int32_t *host = reinterpret_cast<int32_t *>(ctx->scratch) + 1;
+    hipStream_t s = (hipStream_t)stream;
+    FC_HIP(ctx, hipMemcpyAsync(host, dev_err, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    FC_HIP(ctx, hipStreamSynchronize(s));
+    int32_t v = *host;
+    if (v != 0) {
+        int32_t zero = 0;
+        FC_HIP(ctx, hipMemcpyAsync(dev_err, &zero, sizeof zero, hipMemcpyHostToDevice, s));
+        FC_HIP(ctx, hipStreamSynchronize(s));
+        return fc_fail(ctx, FC_ERR_STATE, "device error word = %d (1: head owns too few blocks, 2: id clamped, 4: free list overflow)", v);
+    }
+    return FC_OK;
+}
+
+extern "C" int fc_profile_begin(fc_ctx *ctx)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
+        if (!ctx->prof_ev[i]) FC_HIP(ctx, hipEventCreate(&ctx->prof_ev[i]));
+    ctx->prof_used = 0;
+    ctx->profiling = true;
+    return FC_OK;
+}
+
+extern "C" int fc_profile_end(fc_ctx *ctx, double *avg_attn_kernel_ms, int32_t *launches)
+{
+    if (!ctx || !avg_attn_kernel_ms) return FC_ERR_INVALID_ARG;
+    ctx->profiling = false;
+    double tot = 0.0;
+    for (int i = 0; i < ctx->prof_used; ++i) {
+        FC_HIP(ctx, hipEventSynchronize(ctx->prof_ev[2 * i + 1]));
+        float ms = 0.f;
+        FC_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+        tot += ms;
+    }
+    *avg_attn_kernel_ms = ctx->prof_used ? tot / ctx->prof_used : 0.0;
+    if (launches) *launches = ctx->prof_used;
+    return FC_OK;
+}

@@ -1,0 +1,81 @@
+// Internal declarations shared by the translation units of libflexicache (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "flexicache.h"
+
+constexpr int FC_D = 128;          // head_dim
+constexpr int FC_P = 16;           // tokens per page
+constexpr int FC_PAGE_ELEMS = 2 * FC_P * FC_D;        // bf16 elements per block (K half + V half)
+constexpr int FC_PAGE_BYTES = FC_PAGE_ELEMS * 2;      // 8192
+constexpr int FC_HALF_BYTES = FC_PAGE_BYTES / 2;      // 4096
+constexpr int FC_MM_ROW_BYTES = 2 * FC_D * 2;         // MinMax bytes per page (512)
+constexpr int FC_MAX_PROFILE_EVENTS = 1024;
+
+// Device-side error bits (workspace word `err`).
+constexpr int FC_DEV_ERR_NO_BLOCK = 1;     // a head owned too few blocks for its promoted pages
+constexpr int FC_DEV_ERR_CLAMPED = 2;      // an id outside its valid range was clamped
+constexpr int FC_DEV_ERR_FREE_OVERFLOW = 4;
+
+// Partition of the caller's device workspace.
+struct fc_ws_layout {
+    size_t scores;        // float [max_batch][Hkv][Nmax]
+    size_t seg_start;     // int32 [max_items + 1]
+    size_t plan_meta;     // int32 [8]: 0 = total pages, 1 = pages per wave
+    size_t wave_item;     // int32 [attn_waves]
+    size_t part_ml;       // float [slots][16][2]  (running max in log2 units, running sum)
+    size_t part_acc;      // float [slots][G][128]
+    size_t copy_list;     // int32 [max_items * Kmax][2]
+    size_t counters;      // int32 [8]: 0 = copy count, 1 = err
+    size_t total;
+};
+
+struct fc_ctx {
+    fc_config cfg;
+    int G;
+    int max_items;
+    int attn_waves;
+    int slots;
+    int num_cus;
+    float scale_log2;     // softmax scale times log2(e)
+    char *ws;
+    size_t ws_bytes;
+    char *scratch;        // pinned host scratch
+    size_t scratch_bytes;
+    fc_ws_layout lay;
+    hipEvent_t ev_diff_done;
+    hipEvent_t ev_copies_done;
+    bool copies_pending;
+    // kernel timing
+    bool profiling;
+    int prof_used;
+    hipEvent_t prof_ev[2 * FC_MAX_PROFILE_EVENTS];
+    char err[512];
+};
+
+int fc_fail(fc_ctx *ctx, int status, const char *fmt, ...);
+int fc_hip_fail(fc_ctx *ctx, hipError_t e, const char *what);
+uint64_t fc_stable_mask(const fc_config &cfg, const uint8_t *stable_flag);
+
+#define FC_HIP(ctx, call)                                          \
+    do {                                                           \
+        hipError_t e_ = (call);                                    \
+        if (e_ != hipSuccess) return fc_hip_fail((ctx), e_, #call); \
+    } while (0)
+
+#define FC_REQUIRE(ctx, cond, ...)                                          \
+    do {                                                                    \
+        if (!(cond)) return fc_fail((ctx), FC_ERR_INVALID_ARG, __VA_ARGS__); \
+    } while (0)
+
+template <typename T>
+static inline T *fc_ws_ptr(const fc_ctx *ctx, size_t off)
+{
+    return reinterpret_cast<T *>(ctx->ws + off);
+}
+
+static inline size_t fc_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

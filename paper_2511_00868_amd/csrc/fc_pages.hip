@@ -1,0 +1,103 @@
+// Support kernels: paged-cache writer (token-major K/V -> pool blocks) and MinMax builder (Sec. 3.2).
+#include "fc_internal.h"
+
+// One workgroup per (page, head).  K half is a straight 4 KiB copy (token-major in both places);
+// the V half is transposed to dim-major through LDS.
+__global__ __launch_bounds__(256) void fc_write_pages_kernel(
+    const uint16_t *__restrict__ k_src, const uint16_t *__restrict__ v_src, int n_pages,
+    const int32_t *__restrict__ block_ids, int ids_stride, uint16_t *__restrict__ pool, long long num_blocks)
+{
+    const int page = blockIdx.x, h = blockIdx.y, t = threadIdx.x;
+    const long long blk = block_ids[(size_t)h * ids_stride + page];
+    if (blk <= 0 || blk >= num_blocks) return;
+    const size_t src_off = ((size_t)h * n_pages + page) * (FC_P * FC_D);
+    uint16_t *dst = pool + (size_t)blk * FC_PAGE_ELEMS;
+
+    // K: 256 threads x 16 B
+    reinterpret_cast<uint4 *>(dst)[t] = reinterpret_cast<const uint4 *>(k_src + src_off)[t];
+
+    // V: [16][128] -> [128][16]
+    __shared__ uint16_t tile[FC_P][FC_D + 8];
+    {
+        const int tok = t >> 4, c = t & 15;
+        uint4 x = reinterpret_cast<const uint4 *>(v_src + src_off)[t];
+        *reinterpret_cast<uint4 *>(&tile[tok][c * 8]) = x;
+    }
+    __syncthreads();
+    {
+        const int d = t >> 1, half = t & 1;
+        uint16_t r[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = tile[half * 8 + e][d];
+        uint4 x;
+        x.x = r[0] | ((uint32_t)r[1] << 16);
+        x.y = r[2] | ((uint32_t)r[3] << 16);
+        x.z = r[4] | ((uint32_t)r[5] << 16);
+        x.w = r[6] | ((uint32_t)r[7] << 16);
+        reinterpret_cast<uint4 *>(dst + FC_P * FC_D)[t] = x;   // offset d*16 + half*8 elements = t*8
+    }
+}
+
+// One workgroup per (listed page, head); thread = dimension.
+__global__ __launch_bounds__(128) void fc_minmax_kernel(
+    const uint16_t *__restrict__ pool, long long num_blocks, const int32_t *__restrict__ block_ids,
+    int ids_stride, const int32_t *__restrict__ page_list, int context_len, int n_pages, int max_pages,
+    uint16_t *__restrict__ minmax_seq)
+{
+    const int h = blockIdx.y, d = threadIdx.x;
+    const int page = page_list ? page_list[blockIdx.x] : (int)blockIdx.x;
+    if (page < 0 || page >= n_pages) return;
+    const long long blk = block_ids[(size_t)h * ids_stride + page];
+    if (blk <= 0 || blk >= num_blocks) return;
+    const int ntok = min(FC_P, context_len - page * FC_P);
+    const uint16_t *kp = pool + (size_t)blk * FC_PAGE_ELEMS;
+    uint16_t lo = kp[d], hi = lo;
+    float flo = __uint_as_float((uint32_t)lo << 16), fhi = flo;
+    for (int t = 1; t < ntok; ++t) {
+        uint16_t x = kp[t * FC_D + d];
+        float f = __uint_as_float((uint32_t)x << 16);
+        if (f < flo) { flo = f; lo = x; }
+        if (f > fhi) { fhi = f; hi = x; }
+    }
+    uint16_t *row = minmax_seq + ((size_t)h * max_pages + page) * (2 * FC_D);
+    row[d] = lo;
+    row[FC_D + d] = hi;
+}
+
+extern "C" int fc_write_kv_pages(fc_ctx *ctx, const void *k_src, const void *v_src, int32_t n_pages,
+                                 const int32_t *block_ids, int32_t ids_stride, void *pool,
+                                 int64_t num_blocks, void *stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    FC_REQUIRE(ctx, k_src && v_src && block_ids && pool, "fc_write_kv_pages: NULL pointer");
+    FC_REQUIRE(ctx, n_pages >= 1 && n_pages <= ctx->cfg.max_pages_per_seq, "fc_write_kv_pages: n_pages=%d outside 1..%d", n_pages, ctx->cfg.max_pages_per_seq);
+    FC_REQUIRE(ctx, ids_stride >= n_pages, "fc_write_kv_pages: ids_stride < n_pages");
+    FC_REQUIRE(ctx, num_blocks >= 2, "fc_write_kv_pages: pool needs at least the null block and one more");
+    dim3 grid(n_pages, ctx->cfg.num_kv_heads);
+    hipLaunchKernelGGL(fc_write_pages_kernel, grid, dim3(256), 0, (hipStream_t)stream,
+                       (const uint16_t *)k_src, (const uint16_t *)v_src, n_pages, block_ids, ids_stride,
+                       (uint16_t *)pool, (long long)num_blocks);
+    FC_HIP(ctx, hipGetLastError());
+    return FC_OK;
+}
+
+extern "C" int fc_build_minmax(fc_ctx *ctx, const void *pool, int64_t num_blocks, const int32_t *block_ids,
+                               int32_t ids_stride, const int32_t *page_list, int32_t n_list,
+                               int32_t context_len, void *minmax_seq, void *stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    FC_REQUIRE(ctx, pool && block_ids && minmax_seq, "fc_build_minmax: NULL pointer");
+    FC_REQUIRE(ctx, context_len >= 1, "fc_build_minmax: context_len must be >= 1");
+    const int n_pages = (context_len + FC_P - 1) / FC_P;
+    FC_REQUIRE(ctx, n_pages <= ctx->cfg.max_pages_per_seq, "fc_build_minmax: context of %d pages exceeds max_pages_per_seq", n_pages);
+    FC_REQUIRE(ctx, ids_stride >= n_pages, "fc_build_minmax: ids_stride < pages");
+    FC_REQUIRE(ctx, n_list >= 0 && (page_list || n_list == n_pages), "fc_build_minmax: n_list must equal the page count when page_list is NULL");
+    FC_REQUIRE(ctx, num_blocks >= 2, "fc_build_minmax: pool too small");
+    if (n_list == 0) return FC_OK;
+    dim3 grid(n_list, ctx->cfg.num_kv_heads);
+    hipLaunchKernelGGL(fc_minmax_kernel, grid, dim3(128), 0, (hipStream_t)stream, (const uint16_t *)pool,
+                       (long long)num_blocks, block_ids, ids_stride, page_list, context_len, n_pages,
+                       ctx->cfg.max_pages_per_seq, (uint16_t *)minmax_seq);
+    FC_HIP(ctx, hipGetLastError());
+    return FC_OK;
+}

@@ -1,0 +1,302 @@
+// fc_promote_pages: set difference, physical block recycling, null block, host->HBM page copies
+// (Sec. 3.3 "Minimizing Transfer Size" / "Overlapping Transfer with Compute" / "Reducing
+// Fragmentation Overhead", Sec. 3.4 "Physical Block Reuse During Reranking" and "Uniformity Through
+// Null Block").
+//
+// recycle kernel, one workgroup per (sequence, stable head), on the main stream:
+//   evicted = resident \ new and promoted = new \ resident by binary search in the ascending lists;
+//   the blocks of evicted pages are appended, in ascending page order, to the head's free list;
+//   promoted pages, in ascending page order, take blocks from the front of that list; table entries
+//   of evicted pages become the null block 0; one (host block, HBM block) pair per promoted page is
+//   appended to a global copy list; the rest of the list becomes the new free list.
+// gather kernel, on the side stream after the recycle kernel: a capped number of workgroups walk the
+//   copy list and pull each 8 KiB page straight out of pinned host memory -- no host-side gather, no
+//   per-page API call, no host wait.  (FC_PROMOTE_MEMCPY instead hands the list to the host, which
+//   issues one hipMemcpyAsync per page.)
+#include "fc_internal.h"
+
+constexpr int FC_RECYCLE_THREADS = 256;
+constexpr int FC_GATHER_BLOCKS = 64;     // few workgroups: the copies are PCIe bound and must not
+                                         // crowd the attention kernels off the compute units
+
+struct fc_promote_params {
+    const int32_t *new_pages;
+    const int32_t *new_count;
+    int32_t *resident_pages;
+    int32_t *resident_count;
+    int32_t *block_table;
+    const int32_t *host_block_table;
+    int32_t *free_blocks;
+    int32_t *free_count;
+    const uint8_t *rerank_mask;
+    int32_t *promoted_count;
+    int batch, Hkv, Nmax, Kmax, n_stable;
+    uint8_t heads[64];
+    long long num_pool_blocks, num_host_blocks;
+    int32_t *copy_list;     // device or pinned: pairs (host block, pool block)
+    int32_t *counters;      // device: [0] = pairs appended, [1] = error bits
+    int32_t *host_total;    // pinned, may be NULL
+    int list_capacity;
+};
+
+__device__ __forceinline__ bool fc_sorted_contains(const int32_t *a, int n, int x)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        const int v = a[mid];
+        if (v == x) return true;
+        if (v < x) lo = mid + 1; else hi = mid;
+    }
+    return false;
+}
+
+// Exclusive prefix count of `flag` over the workgroup; `total` gets the workgroup sum.
+__device__ __forceinline__ int fc_block_rank(bool flag, int *wave_cnt, int &total)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const unsigned long long bal = __ballot(flag);
+    if (lane == 0) wave_cnt[wv] = __popcll(bal);
+    __syncthreads();
+    int before = 0;
+    total = 0;
+    for (int k = 0; k < FC_RECYCLE_THREADS / 64; ++k) {
+        const int c = wave_cnt[k];
+        if (k < wv) before += c;
+        total += c;
+    }
+    __syncthreads();
+    return before + __popcll(bal & ((1ull << lane) - 1ull));
+}
+
+__global__ void fc_zero_counter_kernel(int32_t *counters) { counters[0] = 0; }
+
+__global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promote_params p)
+{
+    __shared__ int wave_cnt[FC_RECYCLE_THREADS / 64];
+    __shared__ int sh_list_base;
+    const int b = blockIdx.y;
+    const int h = p.heads[blockIdx.x];
+    const size_t item = (size_t)b * p.Hkv + h;
+    const int tid = threadIdx.x;
+    if (p.rerank_mask && !p.rerank_mask[b]) {
+        if (p.promoted_count && tid == 0) p.promoted_count[item] = 0;
+        return;
+    }
+    int n_old = p.resident_count[item], n_new = p.new_count[item], n_free = p.free_count[item];
+    n_old = min(max(n_old, 0), p.Kmax);
+    n_new = min(max(n_new, 0), p.Kmax);
+    n_free = min(max(n_free, 0), p.Kmax);
+    int32_t *old_l = p.resident_pages + item * (size_t)p.Kmax;
+    const int32_t *new_l = p.new_pages + item * (size_t)p.Kmax;
+    int32_t *tbl = p.block_table + item * (size_t)p.Nmax;
+    const int32_t *htbl = p.host_block_table + item * (size_t)p.Nmax;
+    int32_t *fb = p.free_blocks + item * (size_t)p.Kmax;
+    int err = 0;
+
+    // 1. evicted pages release their blocks to the tail of the free list
+    int pool = n_free;
+    for (int base = 0; base < n_old; base += FC_RECYCLE_THREADS) {
+        const int i = base + tid;
+        int page = -1;
+        bool ev = false;
+        if (i < n_old) {
+            page = old_l[i];
+            ev = page >= 0 && page < p.Nmax && !fc_sorted_contains(new_l, n_new, page);
+        }
+        int tot;
+        const int r = fc_block_rank(ev, wave_cnt, tot);
+        if (ev) {
+            if (pool + r < p.Kmax) fb[pool + r] = tbl[page]; else err |= FC_DEV_ERR_FREE_OVERFLOW;
+            tbl[page] = 0;
+        }
+        pool += tot;
+    }
+    if (pool > p.Kmax) pool = p.Kmax;
+    __threadfence_block();
+    __syncthreads();
+
+    // 2. count promoted pages, reserve a range of the global copy list
+    int n_prom = 0;
+    for (int base = 0; base < n_new; base += FC_RECYCLE_THREADS) {
+        const int i = base + tid;
+        bool pr = false;
+        if (i < n_new) {
+            const int page = new_l[i];
+            pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
+        }
+        int tot;
+        fc_block_rank(pr, wave_cnt, tot);
+        n_prom += tot;
+    }
+    if (tid == 0) sh_list_base = n_prom > 0 ? atomicAdd(&p.counters[0], n_prom) : 0;
+    __syncthreads();
+    const int list_base = sh_list_base;
+
+    // 3. promoted pages take blocks from the front of the free list
+    int taken = 0;
+    for (int base = 0; base < n_new; base += FC_RECYCLE_THREADS) {
+        const int i = base + tid;
+        int page = -1;
+        bool pr = false;
+        if (i < n_new) {
+            page = new_l[i];
+            pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
+        }
+        int tot;
+        const int r = taken + fc_block_rank(pr, wave_cnt, tot);
+        if (pr) {
+            if (r < pool) {
+                long long blk = fb[r];
+                long long hb = htbl[page];
+                if (blk < 1 || blk >= p.num_pool_blocks || hb < 0 || hb >= p.num_host_blocks) {
+                    err |= FC_DEV_ERR_CLAMPED;     // never copy to or from outside the pools
+                    blk = 0;
+                    hb = 0;
+                }
+                tbl[page] = (int32_t)blk;
+                if (list_base + r < p.list_capacity) {
+                    p.copy_list[2 * (size_t)(list_base + r) + 0] = (int32_t)hb;
+                    p.copy_list[2 * (size_t)(list_base + r) + 1] = (int32_t)blk;
+                }
+            } else {
+                err |= FC_DEV_ERR_NO_BLOCK;
+                if (list_base + r < p.list_capacity) {   // keep the list well formed: a no-op pair
+                    p.copy_list[2 * (size_t)(list_base + r) + 0] = 0;
+                    p.copy_list[2 * (size_t)(list_base + r) + 1] = 0;
+                }
+            }
+        }
+        taken += tot;
+    }
+    __syncthreads();
+
+    // 4. what is left of the free list moves to its front
+    const int used = min(taken, pool);
+    const int left = pool - used;
+    for (int base = 0; base < left; base += FC_RECYCLE_THREADS) {   // ascending chunks: reads stay ahead of writes
+        const int i = base + tid;
+        int v = 0;
+        if (i < left) v = fb[used + i];
+        __syncthreads();
+        if (i < left) fb[i] = v;
+        __syncthreads();
+    }
+    // 5. the new list becomes the resident list
+    for (int i = tid; i < p.Kmax; i += FC_RECYCLE_THREADS) old_l[i] = i < n_new ? new_l[i] : -1;
+    if (tid == 0) {
+        p.free_count[item] = left;
+        p.resident_count[item] = n_new;
+        if (p.promoted_count) p.promoted_count[item] = n_prom;
+    }
+    if (err) atomicOr(&p.counters[1], err);
+}
+
+// Publishes the number of pairs where the host can read it (memcpy mode reads it after the event).
+__global__ void fc_publish_total_kernel(const int32_t *counters, int32_t *host_total, int32_t *host_total2)
+{
+    const int v = counters[0];
+    if (host_total) *host_total = v;
+    if (host_total2) *host_total2 = v;
+}
+
+__global__ __launch_bounds__(256) void fc_gather_pages_kernel(const int32_t *__restrict__ copy_list,
+                                                              const int32_t *__restrict__ counters, int list_capacity,
+                                                              const uint4 *__restrict__ host_pool, uint4 *__restrict__ kv_pool)
+{
+    int total = counters[0];
+    total = total > list_capacity ? list_capacity : total;
+    constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
+    for (int i = blockIdx.x; i < total; i += gridDim.x) {
+        const long long src = copy_list[2 * (size_t)i], dst = copy_list[2 * (size_t)i + 1];
+        if (dst <= 0) continue;
+        const uint4 *s = host_pool + src * V;
+        uint4 *d = kv_pool + dst * V;
+        const uint4 x0 = s[threadIdx.x], x1 = s[threadIdx.x + 256];
+        d[threadIdx.x] = x0;
+        d[threadIdx.x + 256] = x1;
+    }
+}
+
+extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *main_stream, void *side_stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    FC_REQUIRE(ctx, a, "fc_promote_pages: args is NULL");
+    FC_REQUIRE(ctx, a->new_pages && a->new_count && a->resident_pages && a->resident_count && a->block_table &&
+                        a->host_block_table && a->free_blocks && a->free_count && a->stable_flag && a->kv_pool && a->host_pool,
+               "fc_promote_pages: NULL pointer among the required arguments");
+    FC_REQUIRE(ctx, a->batch >= 1 && a->batch <= ctx->cfg.max_batch, "fc_promote_pages: batch=%d outside 1..%d", a->batch, ctx->cfg.max_batch);
+    FC_REQUIRE(ctx, a->num_pool_blocks >= 2 && a->num_host_blocks >= 1, "fc_promote_pages: pool sizes must be positive");
+    FC_REQUIRE(ctx, a->mode == FC_PROMOTE_GATHER || a->mode == FC_PROMOTE_MEMCPY, "fc_promote_pages: unknown mode %d", a->mode);
+    FC_REQUIRE(ctx, main_stream != side_stream, "fc_promote_pages: main and side stream must differ");
+
+    fc_promote_params p;
+    p.new_pages = a->new_pages;
+    p.new_count = a->new_count;
+    p.resident_pages = a->resident_pages;
+    p.resident_count = a->resident_count;
+    p.block_table = a->block_table;
+    p.host_block_table = a->host_block_table;
+    p.free_blocks = a->free_blocks;
+    p.free_count = a->free_count;
+    p.rerank_mask = a->rerank_mask;
+    p.promoted_count = a->promoted_count;
+    p.batch = a->batch;
+    p.Hkv = ctx->cfg.num_kv_heads;
+    p.Nmax = ctx->cfg.max_pages_per_seq;
+    p.Kmax = ctx->cfg.max_topk;
+    p.n_stable = 0;
+    memset(p.heads, 0, sizeof p.heads);
+    for (int h = 0; h < p.Hkv; ++h)
+        if (a->stable_flag[h]) p.heads[p.n_stable++] = (uint8_t)h;
+    p.num_pool_blocks = a->num_pool_blocks;
+    p.num_host_blocks = a->num_host_blocks;
+    p.counters = fc_ws_ptr<int32_t>(ctx, ctx->lay.counters);
+    p.host_total = a->total_promoted;
+    p.list_capacity = ctx->max_items * ctx->cfg.max_topk;
+    int32_t *scratch_total = reinterpret_cast<int32_t *>(ctx->scratch);
+    int32_t *scratch_list = reinterpret_cast<int32_t *>(ctx->scratch + 256);
+    p.copy_list = a->mode == FC_PROMOTE_GATHER ? fc_ws_ptr<int32_t>(ctx, ctx->lay.copy_list) : scratch_list;
+
+    hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
+    if (p.n_stable == 0) {
+        if (a->total_promoted) {
+            hipLaunchKernelGGL(fc_zero_counter_kernel, dim3(1), dim3(1), 0, ms, p.counters);
+            hipLaunchKernelGGL(fc_publish_total_kernel, dim3(1), dim3(1), 0, ms, p.counters, a->total_promoted, (int32_t *)nullptr);
+            FC_HIP(ctx, hipGetLastError());
+        }
+        return FC_OK;
+    }
+    if (ctx->copies_pending) {
+        // copies of an earlier call may still be running on the side stream: this call's bookkeeping
+        // must not hand their destination blocks out again before they have landed
+        FC_HIP(ctx, hipStreamWaitEvent(ms, ctx->ev_copies_done, 0));
+        ctx->copies_pending = false;
+    }
+    hipLaunchKernelGGL(fc_zero_counter_kernel, dim3(1), dim3(1), 0, ms, p.counters);
+    hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), 0, ms, p);
+    hipLaunchKernelGGL(fc_publish_total_kernel, dim3(1), dim3(1), 0, ms, p.counters, a->total_promoted, scratch_total);
+    FC_HIP(ctx, hipGetLastError());
+    FC_HIP(ctx, hipEventRecord(ctx->ev_diff_done, ms));
+
+    if (a->mode == FC_PROMOTE_GATHER) {
+        FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
+        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(FC_GATHER_BLOCKS), dim3(256), 0, ss, p.copy_list, p.counters,
+                           p.list_capacity, (const uint4 *)a->host_pool, (uint4 *)a->kv_pool);
+        FC_HIP(ctx, hipGetLastError());
+    } else {
+        FC_HIP(ctx, hipEventSynchronize(ctx->ev_diff_done));   // the one host wait: for the copy list
+        int total = *scratch_total;
+        if (total > p.list_capacity) total = p.list_capacity;
+        const char *hp = (const char *)a->host_pool;
+        char *kp = (char *)a->kv_pool;
+        for (int i = 0; i < total; ++i) {
+            const long long src = scratch_list[2 * i], dst = scratch_list[2 * i + 1];
+            if (dst <= 0) continue;
+            FC_HIP(ctx, hipMemcpyAsync(kp + dst * FC_PAGE_BYTES, hp + src * FC_PAGE_BYTES, FC_PAGE_BYTES, hipMemcpyHostToDevice, ss));
+        }
+    }
+    FC_HIP(ctx, hipEventRecord(ctx->ev_copies_done, ss));
+    ctx->copies_pending = true;
+    return FC_OK;
+}

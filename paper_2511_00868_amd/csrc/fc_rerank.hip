@@ -1,0 +1,253 @@
+// fc_rerank_topk: page scores from the MinMax cache and per-head top-K (Sec. 3.2 of the paper).
+//
+// Score.  max(q_i*kmin_i, q_i*kmax_i) equals q_i*kmax_i when q_i >= 0 and q_i*kmin_i otherwise, so
+// with q+ = max(q, 0) and q- = min(q, 0) the page score of one query is the plain dot product
+//     s_p = [q- | q+] . [kmin_p | kmax_p]           (256 terms, one of every pair is an exact zero)
+// and the scores of 16 pages against the G queries of a group are one 16 x 256 x 16 contraction:
+// 8 x v_mfma_f32_16x16x32_bf16 with A = 16 MinMax rows straight from memory (512 B each, lane reads
+// 16 B of row n at byte 64s + 16j) and B = the sign-split queries.  Products of bf16 values are exact
+// in fp32 and the accumulation is fp32.  The score of the KV head is the maximum over its G queries.
+//
+// Select.  One workgroup per (sequence, stable head): 4-pass 8-bit radix select on the order-
+// preserving integer image of the fp32 score finds the K-th largest key; an index-ordered
+// compaction then emits every page above it plus the lowest-indexed pages equal to it, which is
+// "ties go to the lower page index" and yields the list already ascending.  A partially filled last
+// page gets the largest possible key, so it is always a member and counts toward K (Sec. 3.3).
+#include "fc_internal.h"
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
+
+constexpr int FC_SCORE_TILES_PER_WAVE = 4;                 // 16-page tiles per wavefront
+constexpr int FC_SCORE_PAGES_PER_BLOCK = 4 * FC_SCORE_TILES_PER_WAVE * 16;
+
+struct fc_rerank_params {
+    const uint16_t *q;
+    const char *minmax;
+    const int32_t *context_lens;
+    const int32_t *k_per_seq;
+    const uint8_t *rerank_mask;
+    int batch, Hq, Hkv, G, Nmax, Kmax, n_stable;
+    uint8_t heads[64];
+    float *scores;
+    int32_t *topk_pages;
+    int32_t *topk_count;
+};
+
+struct fc_mm_regs { bf16x8_t a[8]; };
+
+__device__ __forceinline__ void fc_load_mm_tile(fc_mm_regs &r, const char *rows, int page, int last_page, int j)
+{
+    const int pg = page > last_page ? last_page : page;
+    const char *src = rows + (size_t)pg * FC_MM_ROW_BYTES + j * 16;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) r.a[s] = *reinterpret_cast<const bf16x8_t *>(src + s * 64);
+}
+
+__global__ __launch_bounds__(256) void fc_score_kernel(fc_rerank_params p)
+{
+    const int b = blockIdx.z;
+    if (p.rerank_mask && !p.rerank_mask[b]) return;
+    const int h = p.heads[blockIdx.y];
+    const int ctx = p.context_lens[b];
+    int n_pages = (ctx + FC_P - 1) / FC_P;
+    n_pages = n_pages > p.Nmax ? p.Nmax : n_pages;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int page0 = blockIdx.x * FC_SCORE_PAGES_PER_BLOCK + wave * (FC_SCORE_TILES_PER_WAVE * 16);
+    if (page0 >= n_pages) return;
+    const int lane = threadIdx.x & 63, n = lane & 15, j = lane >> 4;
+
+    // B operand: k index 0..127 pairs kmin with q-, 128..255 pairs kmax with q+.
+    bf16x8_t qb[8];
+    {
+        const uint16_t *qrow = p.q + ((size_t)b * p.Hq + (size_t)h * p.G + (n < p.G ? n : 0)) * FC_D;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            short8_t x = *reinterpret_cast<const short8_t *>(qrow + 32 * s + 8 * j);
+            short8_t neg, pos;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool live = n < p.G;
+                neg[e] = (live && x[e] < 0) ? x[e] : (short)0;     // sign bit set <=> negative as int16
+                pos[e] = (live && x[e] >= 0) ? x[e] : (short)0;
+            }
+            qb[s] = __builtin_bit_cast(bf16x8_t, neg);
+            qb[s + 4] = __builtin_bit_cast(bf16x8_t, pos);
+        }
+    }
+    const size_t item = (size_t)b * p.Hkv + h;
+    const char *rows = p.minmax + item * (size_t)p.Nmax * FC_MM_ROW_BYTES;
+    float *score = p.scores + item * (size_t)p.Nmax;
+    const int last_page = n_pages - 1;
+
+    fc_mm_regs buf[2];
+    fc_load_mm_tile(buf[0], rows, page0 + n, last_page, j);
+#pragma unroll
+    for (int t = 0; t < FC_SCORE_TILES_PER_WAVE; ++t) {
+        const int pg = page0 + 16 * t;
+        if (pg >= n_pages) break;
+        if (t + 1 < FC_SCORE_TILES_PER_WAVE && pg + 16 < n_pages)
+            fc_load_mm_tile(buf[(t + 1) & 1], rows, pg + 16 + n, last_page, j);
+        float4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[t & 1].a[k], qb[k], s, 0, 0, 0);
+        // lane (n, j) holds pages pg + 4j + v of query n: maximum over the G queries of the group
+        for (int d = 1; d < p.G; d <<= 1) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) s[v] = fmaxf(s[v], __shfl_xor(s[v], d));
+        }
+        if (n == 0) {
+            const int first = pg + 4 * j;
+            if (first + 3 < n_pages) {
+                *reinterpret_cast<float4_t *>(score + first) = s;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (first + v < n_pages) score[first + v] = s[v];
+            }
+        }
+    }
+}
+
+// ---- select ----------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t fc_order_key(float s)
+{
+    const uint32_t u = __float_as_uint(s);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int FC_SELECT_THREADS = 1024;
+
+__global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_params p)
+{
+    __shared__ int hist[256];
+    __shared__ int wave_cnt[2][FC_SELECT_THREADS / 64];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_remaining;
+
+    const int b = blockIdx.y;
+    if (p.rerank_mask && !p.rerank_mask[b]) return;
+    const int h = p.heads[blockIdx.x];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int ctx = p.context_lens[b];
+    int n = (ctx + FC_P - 1) / FC_P;
+    n = n > p.Nmax ? p.Nmax : (n < 0 ? 0 : n);
+    int K = p.k_per_seq[b];
+    K = K < 0 ? 0 : (K > p.Kmax ? p.Kmax : K);
+    const int want = K < n ? K : n;
+    const int forced = (ctx % FC_P != 0) ? n - 1 : -1;
+    const size_t item = (size_t)b * p.Hkv + h;
+    const float *score = p.scores + item * (size_t)p.Nmax;
+    int32_t *out = p.topk_pages + item * (size_t)p.Kmax;
+
+    auto key_at = [&](int pg) -> uint32_t { return pg == forced ? 0xFFFFFFFFu : fc_order_key(score[pg]); };
+
+    uint32_t T = 0;       // threshold key: pages with key > T are members
+    int need_eq = n;      // how many pages with key == T are members (lowest indices first)
+    if (want < n) {
+        if (tid == 0) { sh_prefix = 0; sh_remaining = want; }
+        uint32_t mask = 0;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const uint32_t prefix = sh_prefix;
+            for (int pg = tid; pg < n; pg += FC_SELECT_THREADS) {
+                const uint32_t k = key_at(pg);
+                if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int rem = sh_remaining, d = 255;
+                for (; d > 0; --d) {
+                    const int c = hist[d];
+                    if (c >= rem) break;
+                    rem -= c;
+                }
+                sh_remaining = rem;
+                sh_prefix = prefix | ((uint32_t)d << shift);
+            }
+            mask |= 0xFFu << shift;
+            __syncthreads();
+        }
+        T = sh_prefix;
+        need_eq = sh_remaining;
+    }
+
+    // index-ordered compaction
+    int eq_base = 0, sel_base = 0;
+    for (int base = 0; base < n; base += FC_SELECT_THREADS) {
+        const int pg = base + tid;
+        bool gt = false, eq = false;
+        if (pg < n) {
+            const uint32_t k = key_at(pg);
+            gt = k > T;
+            eq = k == T;
+        }
+        const unsigned long long beq = __ballot(eq);
+        if (lane == 0) wave_cnt[0][wv] = __popcll(beq);
+        __syncthreads();
+        int eq_before = eq_base, eq_total = 0;
+        for (int k = 0; k < FC_SELECT_THREADS / 64; ++k) {
+            const int c = wave_cnt[0][k];
+            if (k < wv) eq_before += c;
+            eq_total += c;
+        }
+        eq_before += __popcll(beq & ((1ull << lane) - 1ull));
+        const bool sel = gt || (eq && eq_before < need_eq);
+        const unsigned long long bsel = __ballot(sel);
+        if (lane == 0) wave_cnt[1][wv] = __popcll(bsel);
+        __syncthreads();
+        int sel_before = sel_base, sel_total = 0;
+        for (int k = 0; k < FC_SELECT_THREADS / 64; ++k) {
+            const int c = wave_cnt[1][k];
+            if (k < wv) sel_before += c;
+            sel_total += c;
+        }
+        sel_before += __popcll(bsel & ((1ull << lane) - 1ull));
+        if (sel && sel_before < p.Kmax) out[sel_before] = pg;
+        eq_base += eq_total;
+        sel_base += sel_total;
+        __syncthreads();
+    }
+    for (int i = want + tid; i < p.Kmax; i += FC_SELECT_THREADS) out[i] = -1;
+    if (tid == 0) p.topk_count[item] = want;
+}
+
+extern "C" int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *a, void *stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    FC_REQUIRE(ctx, a, "fc_rerank_topk: args is NULL");
+    FC_REQUIRE(ctx, a->q && a->minmax && a->context_lens && a->stable_flag && a->k_per_seq && a->topk_pages && a->topk_count,
+               "fc_rerank_topk: NULL pointer among q, minmax, context_lens, stable_flag, k_per_seq, topk_pages, topk_count");
+    FC_REQUIRE(ctx, a->batch >= 1 && a->batch <= ctx->cfg.max_batch, "fc_rerank_topk: batch=%d outside 1..%d", a->batch, ctx->cfg.max_batch);
+
+    fc_rerank_params p;
+    p.q = (const uint16_t *)a->q;
+    p.minmax = (const char *)a->minmax;
+    p.context_lens = a->context_lens;
+    p.k_per_seq = a->k_per_seq;
+    p.rerank_mask = a->rerank_mask;
+    p.batch = a->batch;
+    p.Hq = ctx->cfg.num_q_heads;
+    p.Hkv = ctx->cfg.num_kv_heads;
+    p.G = ctx->G;
+    p.Nmax = ctx->cfg.max_pages_per_seq;
+    p.Kmax = ctx->cfg.max_topk;
+    p.n_stable = 0;
+    memset(p.heads, 0, sizeof p.heads);
+    for (int h = 0; h < p.Hkv; ++h)
+        if (a->stable_flag[h]) p.heads[p.n_stable++] = (uint8_t)h;
+    p.scores = a->scores_out ? a->scores_out : fc_ws_ptr<float>(ctx, ctx->lay.scores);
+    p.topk_pages = a->topk_pages;
+    p.topk_count = a->topk_count;
+    if (p.n_stable == 0) return FC_OK;
+
+    hipStream_t s = (hipStream_t)stream;
+    dim3 g1((p.Nmax + FC_SCORE_PAGES_PER_BLOCK - 1) / FC_SCORE_PAGES_PER_BLOCK, p.n_stable, p.batch);
+    hipLaunchKernelGGL(fc_score_kernel, g1, dim3(256), 0, s, p);
+    dim3 g2(p.n_stable, p.batch);
+    hipLaunchKernelGGL(fc_select_kernel, g2, dim3(FC_SELECT_THREADS), 0, s, p);
+    FC_HIP(ctx, hipGetLastError());
+    return FC_OK;
+}

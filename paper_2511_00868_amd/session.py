@@ -1,0 +1,192 @@
+"""Decode-loop harness over the C ABI: static placement of one workload's pages (what the paper's
+block allocator would have produced after prefill and offload, Sec. 3.3), then per step
+rerank -> promote -> attend.  Memory plumbing and call sequencing only; every computation is a
+library call."""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import binding
+from .synth import DecodeConfig, Workload
+
+PAGE_ELEMS = 2 * 16 * 128
+
+
+def plan_placement(cfg: DecodeConfig, block_order: np.ndarray):
+    """Host-side static placement.
+
+    Unstable heads get one HBM block per page; a stable head of sequence b gets min(K_b, pages) HBM
+    blocks (its slots, all free at the start) and one host block per page.  Returns
+    (block_table [B,Hkv,Nmax], host_block_table, free_blocks [B,Hkv,Kmax], free_count [B,Hkv],
+    num_pool_blocks, num_host_blocks).  Block 0 of either pool is never handed out."""
+    B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, min(cfg.max_topk, cfg.max_pages)
+    bt = np.zeros((B, H, Nmax), dtype=np.int32)
+    hbt = np.zeros((B, H, Nmax), dtype=np.int32)
+    fb = np.zeros((B, H, Kmax), dtype=np.int32)
+    fc = np.zeros((B, H), dtype=np.int32)
+    nxt, hnxt = 0, 1
+    for b in range(B):
+        n = cfg.num_pages(b)
+        for h in range(H):
+            if cfg.stable[h]:
+                k = min(cfg.topk[b], n)
+                fb[b, h, :k] = block_order[nxt:nxt + k]
+                fc[b, h] = k
+                nxt += k
+                hbt[b, h, :n] = np.arange(hnxt, hnxt + n)
+                hnxt += n
+            else:
+                bt[b, h, :n] = block_order[nxt:nxt + n]
+                nxt += n
+    return bt, hbt, fb, fc, nxt + 1, hnxt
+
+
+def pool_blocks_needed(cfg: DecodeConfig) -> int:
+    tot = 0
+    for b in range(cfg.batch):
+        n = cfg.num_pages(b)
+        for h in range(cfg.num_kv_heads):
+            tot += min(cfg.topk[b], n) if cfg.stable[h] else n
+    return tot
+
+
+class DecodeSession:
+    def __init__(self, cfg: DecodeConfig, wl: Workload, *, device: int = 0, attn_waves: int = 0,
+                 promote_mode: int = binding.FC_PROMOTE_GATHER, keep_scores: bool = False):
+        import torch
+        self.torch = torch
+        self.cfg, self.wl = cfg, wl
+        self.dev = torch.device("cuda", device)
+        self.promote_mode = promote_mode
+        B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, min(cfg.max_topk, cfg.max_pages)
+        self.ctx = binding.Context(num_q_heads=cfg.num_q_heads, num_kv_heads=H, max_batch=B,
+                                   max_pages_per_seq=Nmax, max_topk=Kmax, device=device, attn_waves=attn_waves)
+        order = wl.block_permutation(pool_blocks_needed(cfg))
+        bt, hbt, fb, fc, nblk, nhost = plan_placement(cfg, order)
+        self.num_pool_blocks, self.num_host_blocks = int(nblk), int(max(nhost, 2))
+        i32 = dict(dtype=torch.int32, device=self.dev)
+        self.kv_pool = torch.zeros((self.num_pool_blocks, PAGE_ELEMS), dtype=torch.bfloat16, device=self.dev)
+        self.kv_pool[0].fill_(float("nan"))      # the null block must never influence a result
+        self.host_pool = torch.zeros((self.num_host_blocks, PAGE_ELEMS), dtype=torch.bfloat16, pin_memory=True)
+        self.block_table = torch.from_numpy(bt).to(self.dev)
+        self.host_block_table = torch.from_numpy(hbt).to(self.dev)
+        self.free_blocks = torch.from_numpy(fb).to(self.dev)
+        self.free_count = torch.from_numpy(fc).to(self.dev)
+        self._bt0, self._hbt = bt, hbt
+        self.context_lens = torch.tensor(cfg.ctx, **i32)
+        self.k_per_seq = torch.tensor([min(k, Kmax) for k in cfg.topk], **i32)
+        self.minmax = torch.zeros((B, H, Nmax, 2, 128), dtype=torch.bfloat16, device=self.dev)
+        self.topk_pages = torch.full((B, H, Kmax), -1, **i32)
+        self.topk_count = torch.zeros((B, H), **i32)
+        self.resident_pages = torch.full((B, H, Kmax), -1, **i32)
+        self.resident_count = torch.zeros((B, H), **i32)
+        self.promoted_count = torch.zeros((B, H), **i32)
+        self.total_promoted = torch.zeros(1, dtype=torch.int32, pin_memory=True)
+        self.scores = torch.zeros((B, H, Nmax), dtype=torch.float32, device=self.dev) if keep_scores else None
+        self.q = torch.zeros((B, cfg.num_q_heads, 128), dtype=torch.bfloat16, device=self.dev)
+        self.out = torch.zeros((B, cfg.num_q_heads, 128), dtype=torch.float32, device=self.dev)
+        self.lse = torch.zeros((B, cfg.num_q_heads), dtype=torch.float32, device=self.dev)
+        self.main = torch.cuda.current_stream(self.dev)
+        self.side = torch.cuda.Stream(self.dev)            # default priority
+        self.stable = list(cfg.stable)
+        for b in range(B):
+            self._write_sequence(b, None)
+        torch.cuda.synchronize(self.dev)
+
+    # ---- placement of page contents ---------------------------------------------------------------
+    def _bits_to_dev(self, a: np.ndarray):
+        return self.torch.from_numpy(a.view(np.int16)).to(self.dev).view(self.torch.bfloat16)
+
+    def _write_sequence(self, b: int, only: Optional[Dict[int, Sequence[int]]]):
+        """(Re)writes pages of sequence b from the master copy: `only` = {head: pages} or None = all."""
+        torch, cfg = self.torch, self.cfg
+        n = cfg.num_pages(b)
+        kd, vd = self._bits_to_dev(self.wl.k[b]), self._bits_to_dev(self.wl.v[b])
+        sel = np.zeros((cfg.num_kv_heads, n), dtype=bool)
+        if only is None:
+            sel[:] = True
+        else:
+            for h, pages in only.items():
+                sel[h, list(pages)] = True
+        hbm_ids = np.where(sel, self._current_table(b)[:, :n], 0).astype(np.int32)
+        host_ids = np.where(sel, self._hbt[b][:, :n], 0).astype(np.int32)
+        hbm_ids_d = torch.from_numpy(np.ascontiguousarray(hbm_ids)).to(self.dev)
+        host_ids_d = torch.from_numpy(np.ascontiguousarray(host_ids)).to(self.dev)
+        c = self.ctx
+        c.fc_write_kv_pages(kd, vd, n, hbm_ids_d, self.kv_pool, self.num_pool_blocks, self.main)
+        if any(self.stable):
+            c.fc_write_kv_pages(kd, vd, n, host_ids_d, self.host_pool, self.num_host_blocks, self.main)
+        # MinMax rows: from the HBM copy for unstable heads, from the host copy for stable heads
+        if only is None:
+            plist, nl = None, n
+        else:
+            pages = sorted({p for ps in only.values() for p in ps})
+            plist, nl = torch.tensor(pages, dtype=torch.int32, device=self.dev), len(pages)
+        unst = np.where(np.array(self.stable)[:, None], 0, self._bt0[b][:, :n]).astype(np.int32)
+        c.fc_build_minmax(self.kv_pool, self.num_pool_blocks, torch.from_numpy(np.ascontiguousarray(unst)).to(self.dev),
+                          plist, nl, cfg.ctx[b], self.minmax[b], self.main)
+        if any(self.stable):
+            hst = torch.from_numpy(np.ascontiguousarray(self._hbt[b][:, :n])).to(self.dev)
+            c.fc_build_minmax(self.host_pool, self.num_host_blocks, hst, plist, nl, cfg.ctx[b], self.minmax[b],
+                              self.main)
+        torch.cuda.synchronize(self.dev)   # kd / vd die with this frame
+
+    def _current_table(self, b: int) -> np.ndarray:
+        return self.block_table[b].cpu().numpy()
+
+    def refresh(self, changed: List[Tuple[int, int, List[int]]]):
+        """Pushes master-copy changes (hot pages planted or retired) to every copy of those pages."""
+        per_seq: Dict[int, Dict[int, List[int]]] = {}
+        for b, h, pages in changed:
+            per_seq.setdefault(b, {})[h] = pages
+        for b, only in per_seq.items():
+            self._write_sequence(b, only)
+
+    # ---- the three hot-path calls -------------------------------------------------------------------
+    def set_queries(self, q_bits: np.ndarray):
+        self.q.copy_(self._bits_to_dev(q_bits))
+
+    def rerank(self, rerank_mask=None):
+        self.ctx.fc_rerank_topk(q=self.q, minmax=self.minmax, context_lens=self.context_lens,
+                                stable_flag=self.stable, k_per_seq=self.k_per_seq, batch=self.cfg.batch,
+                                topk_pages=self.topk_pages, topk_count=self.topk_count, rerank_mask=rerank_mask,
+                                scores_out=self.scores, stream=self.main)
+
+    def promote(self, rerank_mask=None):
+        self.ctx.fc_promote_pages(new_pages=self.topk_pages, new_count=self.topk_count,
+                                  resident_pages=self.resident_pages, resident_count=self.resident_count,
+                                  block_table=self.block_table, host_block_table=self.host_block_table,
+                                  free_blocks=self.free_blocks, free_count=self.free_count,
+                                  stable_flag=self.stable, kv_pool=self.kv_pool,
+                                  num_pool_blocks=self.num_pool_blocks, host_pool=self.host_pool,
+                                  num_host_blocks=self.num_host_blocks, batch=self.cfg.batch,
+                                  main_stream=self.main, side_stream=self.side, mode=self.promote_mode,
+                                  rerank_mask=rerank_mask, promoted_count=self.promoted_count,
+                                  total_promoted=self.total_promoted)
+
+    def attend(self):
+        self.ctx.fc_sparse_decode_attn(q=self.q, kv_pool=self.kv_pool, num_pool_blocks=self.num_pool_blocks,
+                                       block_table=self.block_table, context_lens=self.context_lens,
+                                       stable_flag=self.stable, topk_pages=self.resident_pages,
+                                       topk_count=self.resident_count, batch=self.cfg.batch, out=self.out,
+                                       lse=self.lse, stream=self.main)
+
+    def step(self, t: int):
+        """One pass of the hot path for decode step t (queries already set)."""
+        if self.cfg.is_rerank_step(t) and any(self.stable):
+            self.rerank()
+            self.promote()
+        self.attend()
+
+    def selected(self) -> Dict[Tuple[int, int], np.ndarray]:
+        pages = self.resident_pages.cpu().numpy()
+        cnt = self.resident_count.cpu().numpy()
+        return {(b, h): pages[b, h, :cnt[b, h]].copy() for b in range(self.cfg.batch)
+                for h in range(self.cfg.num_kv_heads) if self.stable[h]}
+
+    def close(self):
+        self.torch.cuda.synchronize(self.dev)
+        self.ctx.close()

@@ -1,0 +1,70 @@
+"""GPU parity tests: the HIP library (through its C ABI) against the CPU oracle."""
+import numpy as np
+import pytest
+
+from paper_2511_00868_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(cfg, **kw):
+    from parity_util import ParityRun
+    r = ParityRun(cfg, **kw)
+    try:
+        r.run()
+        return r
+    finally:
+        r.close()
+
+
+def test_config1_tiny_full_loop():
+    r = _run(synth.make_config(1))
+    assert r.promoted_total >= 8          # the cold fill alone promotes K = 8 pages
+
+
+@pytest.mark.parametrize("mode", [binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_MEMCPY])
+def test_config2_reduced_both_promotion_modes(mode):
+    # 4096-token contexts: 256 pages, K = 25; several wavefront shares per head and ragged tails
+    _run(synth.make_config(2, batch=3, ctx=4096 + 7, steps=6), promote_mode=mode)
+
+
+def test_config3_reduced_drift():
+    _run(synth.make_config(3, batch=2, ctx=16384, steps=17))
+
+
+def test_config4_reduced_ragged_shuffled():
+    _run(synth.make_config(4, batch=9, ctx=6000, steps=5))
+
+
+def test_config5_reduced_planted_promotions():
+    r = _run(synth.make_config(5, batch=3, ctx=8192, steps=9))
+    assert r.promoted_total > 3 * 5 * 32   # more than the cold fill: planted pages forced promotions
+
+
+@pytest.mark.parametrize("ctx,K", [(1, 1), (15, 1), (16, 1), (17, 2), (33, 1), (100, 64), (1000, 5)])
+def test_edge_context_lengths_and_budgets(ctx, K):
+    import dataclasses
+    cfg = synth.make_config(1, ctx=ctx, steps=3)
+    n = -(-ctx // 16)
+    cfg = dataclasses.replace(cfg, topk=(K,), hot_per_head=min(2, n), name=f"edge_{ctx}_{K}")
+    _run(cfg)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(2, 2), (4, 2), (16, 2), (32, 2)])
+def test_group_sizes(Hq, Hkv):
+    import dataclasses
+    cfg = dataclasses.replace(synth.make_config(1, ctx=1500, steps=3), num_q_heads=Hq, num_kv_heads=Hkv,
+                              name=f"group_{Hq // Hkv}")
+    _run(cfg)
+
+
+def test_few_wavefronts_many_items_per_wavefront():
+    # 8 wavefronts over 9 sequences x 8 heads: every wavefront crosses several item boundaries
+    _run(synth.make_config(4, batch=9, ctx=3000, steps=2), attn_waves=8)
+
+
+def test_all_heads_stable_and_all_heads_unstable():
+    import dataclasses
+    base = synth.make_config(2, batch=2, ctx=3000, steps=5)
+    _run(dataclasses.replace(base, stable=(True,) * 8, name="all_stable"))
+    _run(dataclasses.replace(base, stable=(False,) * 8, dynamics="static", name="all_unstable"))
