@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the FlexiCache decode hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch: on rerank steps fc_rerank_topk +
+fc_promote_pages, then always fc_sparse_decode_attn.  All inputs (pool, tables, MinMax cache, every
+step's queries) are resident in HBM before the timed region; the host pool sits in pinned memory.
+Prints one JSON line."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def attention_bytes(cfg) -> int:
+    """Algorithmic bytes one fc_sparse_decode_attn call must move: per attended page its valid tokens'
+    K and V (512 B per token) and its 4 B table entry (+4 B list entry for a stable head); per
+    (sequence, query head) 256 B of query and 512 B of fp32 output."""
+    tot = 0
+    for b in range(cfg.batch):
+        n = cfg.num_pages(b)
+        tail = cfg.ctx[b] - 16 * (n - 1)
+        for h in range(cfg.num_kv_heads):
+            if cfg.stable[h]:
+                k = min(cfg.topk[b], n)
+                # the partial last page is always a member of a stable head's set
+                toks = 16 * k - ((16 - tail) if tail < 16 else 0)
+                tot += 512 * toks + 8 * k
+            else:
+                tot += 512 * cfg.ctx[b] + 4 * n
+        tot += cfg.num_q_heads * (256 + 512)
+    return tot
+
+
+def rerank_bytes(cfg) -> int:
+    """512 B of MinMax per page of every reranking (sequence, stable head), its queries, 4 B per selected page."""
+    tot = 0
+    for b in range(cfg.batch):
+        n = cfg.num_pages(b)
+        for h in range(cfg.num_kv_heads):
+            if cfg.stable[h]:
+                tot += 512 * n + cfg.group * 256 + 4 * min(cfg.topk[b], n)
+    return tot
+
+
+def cpu_baseline(cfg, wl, budget_s: float = 20.0):
+    """Times the CPU oracle, as it stands, on whole decode steps of the same workload until about
+    `budget_s` seconds of work have been done (at least one step)."""
+    import oracle
+    dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, cfg.topk,
+                               cfg.rerank_interval)
+    mm = [oracle.seq_build_minmax(wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]   # untimed: an input
+    t0 = time.perf_counter()
+    nbytes, steps = 0, 0
+    while True:
+        q = wl.queries(steps)
+        if cfg.is_rerank_step(steps):
+            for b in range(cfg.batch):
+                dec.rerank(b, q[b], mm[b])
+            nbytes += rerank_bytes(cfg)
+        for b in range(cfg.batch):
+            dec.attend(b, q[b], wl.k[b], wl.v[b])
+        nbytes += attention_bytes(cfg)
+        steps += 1
+        el = time.perf_counter() - t0
+        if el > budget_s or steps >= cfg.steps or el * (steps + 1) / steps > 1.5 * budget_s:
+            break
+    return {"value": nbytes / el / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{steps} whole decode step(s) of {cfg.name} (all {cfg.batch} sequences, rerank on step 0), "
+                      f"{el:.1f} s", "s_per_step": el / steps}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (default: the one the metric is quoted on)")
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--ctx", type=int, default=None)
+    ap.add_argument("--promote-mode", choices=["gather", "memcpy"], default="gather")
+    ap.add_argument("--attn-waves", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="run rerank, promotion and attention back to back on one stream")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards by sequence or KV head with no "
+              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2511_00868_amd import binding, synth
+    from paper_2511_00868_amd.session import DecodeSession
+
+    total_steps = args.warmup + args.steps
+    cfg = synth.make_config(args.config, batch=args.batch, ctx=args.ctx, steps=total_steps)
+    t_gen = time.perf_counter()
+    wl = synth.Workload(cfg)
+    mode = binding.FC_PROMOTE_GATHER if args.promote_mode == "gather" else binding.FC_PROMOTE_MEMCPY
+    sess = DecodeSession(cfg, wl, promote_mode=mode, attn_waves=args.attn_waves)
+    q_all = torch.stack([sess._bits_to_dev(wl.queries(t)) for t in range(total_steps)])
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+
+    sess.overlap = not args.no_overlap
+    main = torch.cuda.current_stream()
+
+    def run_step(t, marks=None):
+        sess.q = q_all[t]
+        if marks is not None:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record(main)
+            marks.append(e)
+        sess.step(t)
+
+    for t in range(args.warmup):
+        run_step(t)
+    torch.cuda.synchronize()
+    sess.ctx.fc_check_device_state()
+
+    marks = []
+    sess.ctx.fc_profile_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup, total_steps):
+        run_step(t, marks)
+    e_end = torch.cuda.Event(enable_timing=True)
+    e_end.record(main)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    attn_ms, launches = sess.ctx.fc_profile_end()
+    sess.ctx.fc_check_device_state()
+    marks.append(e_end)
+    step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps)]
+    is_rer = [cfg.is_rerank_step(t) and any(cfg.stable) for t in range(args.warmup, total_steps)]
+    rer_us = [u for u, r in zip(step_us, is_rer) if r]
+    plain_us = [u for u, r in zip(step_us, is_rer) if not r]
+    promoted_last = int(sess.total_promoted[0])
+
+    n_rerank = len(rer_us)
+    a_bytes, r_bytes = attention_bytes(cfg), rerank_bytes(cfg)
+    step_bytes = a_bytes * args.steps + r_bytes * n_rerank
+    value = step_bytes / elapsed / 1e9
+    # a rerank step launches the kernel twice (unstable heads, then stable heads): bytes per launch is the
+    # average over all launches of the timed region, as is the duration
+    bytes_per_launch = a_bytes * args.steps / max(launches, 1)
+    ach = bytes_per_launch / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
+    out = {
+        "metric": "sparse decode attention effective HBM GB/s (% of peak) + rerank us/step",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "context": max(cfg.ctx), "q_heads": cfg.num_q_heads,
+                   "kv_heads": cfg.num_kv_heads, "stable_heads": int(sum(cfg.stable)), "topk_pages": cfg.max_topk,
+                   "rerank_interval": cfg.rerank_interval, "pages_attended_per_step": cfg.pages_attended(),
+                   "promote_mode": args.promote_mode, "attn_wavefronts": sess.ctx.cfg.attn_waves or "auto"},
+        "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
+        "attn_bytes_per_step": a_bytes, "rerank_bytes_per_invocation": r_bytes,
+        "step_us_plain_median": round(float(np.median(plain_us)), 2) if plain_us else None,
+        "step_us_rerank_median": round(float(np.median(rer_us)), 2) if rer_us else None,
+        "rerank_exposed_us_per_step_amortised": round((float(np.median(rer_us)) - float(np.median(plain_us))) * n_rerank
+                                                      / args.steps, 2) if rer_us and plain_us else None,
+        "rerank_invocations": n_rerank, "promoted_pages_last_rerank": promoted_last,
+        "overlap_rerank_with_unstable_heads": sess.overlap,
+        "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "fc_decode_attn_kernel",
+                     "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,
+                     "algorithmic_bytes_per_launch": int(bytes_per_launch)},
+        "setup_s": round(t_gen, 1),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_budget)
+    sess.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

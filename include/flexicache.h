@@ -177,7 +177,12 @@ int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream
  * stable, all pages 0..ceil(context_len/16)-1 otherwise; each of the G query heads of the group gets
  *   out = softmax(scale * q . K_set^T) V_set   over tokens < context_len, fp32,
  *   lse = natural-log-sum-exp of the scaled logits (optional).
- * Every page of the set must be resident (block_table entry != 0). */
+ * Every page of the set must be resident (block_table entry != 0).
+ * head_subset restricts the call to one class of heads, leaving the output rows of the other class
+ * untouched: a caller that has just promoted pages can run FC_HEADS_UNSTABLE (which does not depend
+ * on the copies, and does not wait for them) while they are in flight and FC_HEADS_STABLE afterwards
+ * (Sec. 3.3 "Overlapping Transfer with Compute"). */
+enum { FC_HEADS_ALL = 0, FC_HEADS_UNSTABLE = 1, FC_HEADS_STABLE = 2 };
 typedef struct {
     const void *q;               /* dev bf16 [batch][num_q_heads][D] */
     const void *kv_pool;         /* dev */
@@ -190,6 +195,7 @@ typedef struct {
     int32_t batch;
     float *out;                  /* dev out fp32 [batch][num_q_heads][D] */
     float *lse;                  /* dev out fp32 [batch][num_q_heads] or NULL */
+    int32_t head_subset;         /* FC_HEADS_ALL | FC_HEADS_UNSTABLE | FC_HEADS_STABLE */
 } fc_attn_args;
 int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
 
@@ -198,7 +204,7 @@ int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
  * FC_ERR_STATE. */
 int fc_check_device_state(fc_ctx *ctx, void *stream);
 
-/* Average duration in milliseconds of the dominant attention kernel (the split-KV partial kernel)
+/* Average duration in milliseconds of the dominant kernel (the decode attention kernel)
  * between two calls, measured with HIP events on the stream it was launched on; used by
  * benchmarks.  fc_profile_begin arms it, fc_profile_end synchronises and reports. */
 int fc_profile_begin(fc_ctx *ctx);

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(HERE, "libflexicache.so")
 
 FC_OK, FC_ERR_INVALID_ARG, FC_ERR_UNSUPPORTED, FC_ERR_WORKSPACE, FC_ERR_HIP, FC_ERR_STATE = 0, -1, -2, -3, -4, -5
 FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY = 0, 1
+FC_HEADS_ALL, FC_HEADS_UNSTABLE, FC_HEADS_STABLE = 0, 1, 2
 
 EXPORTS = ["fc_workspace_bytes", "fc_host_scratch_bytes", "fc_create", "fc_destroy", "fc_status_string",
            "fc_last_error", "fc_write_kv_pages", "fc_build_minmax", "fc_rerank_topk", "fc_promote_pages",
@@ -45,7 +46,7 @@ class fc_attn_args(C.Structure):
     _fields_ = [("q", C.c_void_p), ("kv_pool", C.c_void_p), ("num_pool_blocks", C.c_int64),
                 ("block_table", C.c_void_p), ("context_lens", C.c_void_p), ("stable_flag", C.c_void_p),
                 ("topk_pages", C.c_void_p), ("topk_count", C.c_void_p), ("batch", C.c_int32),
-                ("out", C.c_void_p), ("lse", C.c_void_p)]
+                ("out", C.c_void_p), ("lse", C.c_void_p), ("head_subset", C.c_int32)]
 
 
 _lib = None
@@ -178,10 +179,11 @@ class Context:
                                               self._stream(side_stream)))
 
     def fc_sparse_decode_attn(self, *, q, kv_pool, num_pool_blocks: int, block_table, context_lens, stable_flag,
-                              topk_pages, topk_count, batch: int, out, lse=None, stream=None):
+                              topk_pages, topk_count, batch: int, out, lse=None, head_subset: int = FC_HEADS_ALL,
+                              stream=None):
         flags = _host_u8(stable_flag)
         a = fc_attn_args(_ptr(q), _ptr(kv_pool), num_pool_blocks, _ptr(block_table), _ptr(context_lens),
-                         C.addressof(flags), _ptr(topk_pages), _ptr(topk_count), batch, _ptr(out), _ptr(lse))
+                         C.addressof(flags), _ptr(topk_pages), _ptr(topk_count), batch, _ptr(out), _ptr(lse), head_subset)
         self._check(self.lib.fc_sparse_decode_attn(self.handle, C.byref(a), self._stream(stream)))
 
     def fc_check_device_state(self, stream=None):

@@ -1,16 +1,16 @@
 // fc_sparse_decode_attn: head-heterogeneous paged decode attention (Sec. 3.1 of the paper; the
 // split-KV + merge structure of decode attention named in Sec. 4.1).
 //
-// Three kernels per call:
-//   plan     one workgroup: page count of every (sequence, KV head) item -- all pages for an unstable
-//            head, the top-K count for a stable one -- prefix sums over items, the number of pages
-//            each wavefront takes (total / wavefronts, rounded up) and each wavefront's first item.
-//   partial  every wavefront streams its equal share of the concatenated page lists, independent of
-//            item boundaries, so a 2048-page unstable head and a 204-page stable head cost the
-//            same per page and no wavefront is left with a long tail.  Per page: QK^T and PV on
-//            the matrix cores, online softmax in registers.  One partial (m, l, acc) per
-//            (wavefront, item) pair it touches.
-//   merge    one workgroup per item: log-sum-exp combination of that item's partials.
+// Two kernels per call.  In the first, every workgroup first derives the same schedule: the page count of every
+// (sequence, KV head) item -- all pages for an unstable head, the top-K count for a stable one --
+// and their prefix sums (kept in LDS).  The concatenated page lists are cut into equal shares, one
+// per wavefront, independent of item boundaries, so a 2048-page unstable head and a 204-page stable
+// head cost the same per page and no wavefront is left with a long tail.  Per page: QK^T and PV on
+// the matrix cores, online softmax in registers.  A wavefront that saw a whole item writes the
+// result directly; otherwise it leaves a partial (m, l, acc), and a second, small kernel combines
+// the partials of every split item (log-sum-exp merge).  (Combining inside the first kernel by the
+// last wavefront to arrive was tried and was twice as slow: every wavefront then pays a device-scope
+// release fence, and the lone merging wavefront serialises the tail.)
 //
 // Matrix-core mapping (wave64, 16x16 tiles; lane = 16*j + n):
 //   S^T[key][query] = K_page[16 x 128] . Q^T[128 x 16]   4 x v_mfma_f32_16x16x32_bf16
@@ -40,12 +40,11 @@ struct fc_attn_params {
     const int32_t *topk_pages;
     const int32_t *topk_count;
     unsigned long long stable_mask;
+    unsigned long long active_mask;   // heads this call covers
     int batch, Hq, Hkv, G, Nmax, Kmax;
     int n_waves;
     float scale_log2;
-    int32_t *seg_start;
-    int32_t *plan_meta;
-    int32_t *wave_item;
+    int32_t *seg_start;   // [items + 2]: prefix sums, then pages per wavefront
     float *part_ml;
     float *part_acc;
     float *out;
@@ -56,65 +55,6 @@ __device__ __forceinline__ int fc_pages_of(int ctx, int Nmax)
 {
     int n = (ctx + FC_P - 1) / FC_P;
     return n < 0 ? 0 : (n > Nmax ? Nmax : n);
-}
-
-// ---- plan ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void fc_attn_plan_kernel(fc_attn_params p)
-{
-    __shared__ int wave_tot[16];
-    __shared__ int carry;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int items = p.batch * p.Hkv;
-    if (tid == 0) { carry = 0; p.seg_start[0] = 0; }
-    __syncthreads();
-    for (int base = 0; base < items; base += 1024) {
-        const int i = base + tid;
-        int cnt = 0;
-        if (i < items) {
-            const int b = i / p.Hkv, h = i - b * p.Hkv;
-            const int n = fc_pages_of(p.context_lens[b], p.Nmax);
-            if ((p.stable_mask >> h) & 1ull) {
-                int k = p.topk_count[i];
-                cnt = k < 0 ? 0 : (k > n ? n : k);
-                if (cnt > p.Kmax) cnt = p.Kmax;
-            } else {
-                cnt = n;
-            }
-        }
-        int x = cnt;   // inclusive scan inside the wavefront
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            int y = __shfl_up(x, d);
-            if (lane >= d) x += y;
-        }
-        if (lane == 63) wave_tot[wv] = x;
-        __syncthreads();
-        int off = carry;
-        for (int k = 0; k < wv; ++k) off += wave_tot[k];
-        if (i < items) p.seg_start[i + 1] = off + x;
-        __syncthreads();
-        if (tid == 1023) carry = off + x;
-        __syncthreads();
-    }
-    const int total = carry;
-    int L = (total + p.n_waves - 1) / p.n_waves;
-    if (L < FC_MIN_PAGES_PER_WAVE) L = FC_MIN_PAGES_PER_WAVE;
-    if (tid == 0) { p.plan_meta[0] = total; p.plan_meta[1] = L; }
-    __threadfence_block();
-    __syncthreads();
-    for (int w = tid; w < p.n_waves; w += 1024) {
-        const long long start = (long long)w * L;
-        int it = -1;
-        if (start < total) {   // last item whose first page is <= start and that is not empty
-            int lo = 0, hi = items;            // find the item with seg_start[it] <= start < seg_start[it+1]
-            while (hi - lo > 1) {
-                int mid = (lo + hi) >> 1;
-                if (p.seg_start[mid] <= start) lo = mid; else hi = mid;
-            }
-            it = lo;
-        }
-        p.wave_item[w] = it;
-    }
 }
 
 // ---- partial ---------------------------------------------------------------------------------------
@@ -187,22 +127,91 @@ __device__ __forceinline__ void fc_consume_page(fc_softmax_state &st, fc_page_re
     }
 }
 
-__global__ __launch_bounds__(256, 2) void fc_attn_partial_kernel(fc_attn_params p)
+// Writes the final result of one (sequence, KV head) item for query column n of this lane.
+__device__ __forceinline__ void fc_store_final(const fc_attn_params &p, size_t row, int n, int j, float m, float l,
+                                               const float4_t (&acc)[8])
 {
-    const int lane = threadIdx.x & 63;
-    const int w = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int item = p.wave_item[w];
-    if (item < 0) return;
-    const int total = p.plan_meta[0], L = p.plan_meta[1];
+    if (n < p.G) {
+        const float inv = 1.0f / l;
+        float *dst = p.out + (row + n) * FC_D + 4 * j;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) *reinterpret_cast<float4_t *>(dst + 16 * c) = acc[c] * inv;
+        if (p.lse && j == 0) p.lse[row + n] = (m + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    }
+}
+
+__global__ __launch_bounds__(256, 2) void fc_decode_attn_kernel(fc_attn_params p)
+{
+    __shared__ int seg[FC_MAX_ITEMS + 1];     // seg[i] = first page of item i in the concatenated order
+    __shared__ int wave_tot[4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int items = p.batch * p.Hkv;
+
+    // ---- schedule: every workgroup derives the same page counts and prefix sums -------------------
+    {
+        int carry = 0;
+        if (tid == 0) seg[0] = 0;
+        for (int base = 0; base < items; base += 256) {
+            const int i = base + tid;
+            int cnt = 0;
+            if (i < items) {
+                const int b = i / p.Hkv, h = i - b * p.Hkv;
+                const int n = fc_pages_of(p.context_lens[b], p.Nmax);
+                if (!((p.active_mask >> h) & 1ull)) {
+                    cnt = 0;
+                } else if ((p.stable_mask >> h) & 1ull) {
+                    const int k = p.topk_count[i];
+                    cnt = k < 0 ? 0 : (k > n ? n : k);
+                    if (cnt > p.Kmax) cnt = p.Kmax;
+                } else {
+                    cnt = n;
+                }
+            }
+            int x = cnt;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(x, d);
+                if (lane >= d) x += y;
+            }
+            if (lane == 63) wave_tot[wv] = x;
+            __syncthreads();
+            int off = carry;
+            for (int k = 0; k < 4; ++k) {
+                const int c = wave_tot[k];
+                if (k < wv) off += c;
+                carry += c;
+            }
+            if (i < items) seg[i + 1] = off + x;
+            __syncthreads();
+        }
+    }
+    const int total = seg[items];
+    int L = (total + p.n_waves - 1) / p.n_waves;
+    if (L < FC_MIN_PAGES_PER_WAVE) L = FC_MIN_PAGES_PER_WAVE;
+    if (blockIdx.x == 0) {                    // the merge kernel reads the schedule from memory
+        for (int i = tid; i <= items; i += 256) p.seg_start[i] = seg[i];
+        if (tid == 0) p.seg_start[items + 1] = L;
+    }
+    const int w = blockIdx.x * 4 + wv;
     int g0 = w * L;
     const int g1 = min(g0 + L, total);
+    if (g0 >= g1) return;
+    int item;
+    {   // the item with seg[item] <= g0 < seg[item + 1]
+        int lo = 0, hi = items;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (seg[mid] <= g0) lo = mid; else hi = mid;
+        }
+        item = lo;
+    }
     const int n = lane & 15, j = lane >> 4;
     const int lane_k_off = n * 256 + j * 16;
     const int lane_v_off = n * 32 + j * 8;
-    const int items = p.batch * p.Hkv;
 
     while (g0 < g1 && item < items) {
-        const int s0 = p.seg_start[item], s1 = p.seg_start[item + 1];
+        const int s0 = seg[item], s1 = seg[item + 1];
         if (s1 <= g0) { ++item; continue; }             // empty item
         const int lo = g0 - s0, hi = min(g1, s1) - s0;
         const int b = item / p.Hkv, h = item - b * p.Hkv;
@@ -262,15 +271,22 @@ __global__ __launch_bounds__(256, 2) void fc_attn_partial_kernel(fc_attn_params 
         float l = st.l;
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        const int slot = w + item;
-        if (n < p.G) {
-            if (j == 0) {
-                p.part_ml[((size_t)slot * 16 + n) * 2 + 0] = st.m;
-                p.part_ml[((size_t)slot * 16 + n) * 2 + 1] = l;
-            }
-            float *dst = p.part_acc + ((size_t)slot * p.G + n) * FC_D + 4 * j;
+
+        const size_t row = (size_t)b * p.Hq + (size_t)h * p.G;
+        const int w_first = s0 / L, w_last = (s1 - 1) / L;
+        if (w_first == w_last) {
+            fc_store_final(p, row, n, j, st.m, l, st.acc);           // this wavefront saw the whole item
+        } else {
+            const int slot = w + item;
+            if (n < p.G) {
+                if (j == 0) {
+                    p.part_ml[((size_t)slot * 16 + n) * 2 + 0] = st.m;
+                    p.part_ml[((size_t)slot * 16 + n) * 2 + 1] = l;
+                }
+                float *dst = p.part_acc + ((size_t)slot * p.G + n) * FC_D + 4 * j;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) *reinterpret_cast<float4_t *>(dst + 16 * c) = st.acc[c];
+                for (int c = 0; c < 8; ++c) *reinterpret_cast<float4_t *>(dst + 16 * c) = st.acc[c];
+            }
         }
         g0 = s0 + hi;
         ++item;
@@ -278,34 +294,59 @@ __global__ __launch_bounds__(256, 2) void fc_attn_partial_kernel(fc_attn_params 
 }
 
 // ---- merge -----------------------------------------------------------------------------------------
+// One workgroup per item that was split over several wavefronts; wavefront g % 4 combines query g.
+// Lanes first run over the partials (maximum and weights), then over the output: lane = (half, d4)
+// accumulates the partials of its half, weights broadcast by lane shuffle.
 __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
 {
     const int item = blockIdx.x;
+    const int items = p.batch * p.Hkv;
+    const int s0 = p.seg_start[item], s1 = p.seg_start[item + 1], L = p.seg_start[items + 1];
     const int b = item / p.Hkv, h = item - b * p.Hkv;
-    const int s0 = p.seg_start[item], s1 = p.seg_start[item + 1];
-    const int L = p.plan_meta[1];
-    const int w_first = s0 / L, w_last = s1 > s0 ? (s1 - 1) / L : w_first - 1;
-    for (int o = threadIdx.x; o < p.G * (FC_D / 4); o += blockDim.x) {
-        const int g = o / (FC_D / 4), d4 = o - g * (FC_D / 4);
+    const size_t row = (size_t)b * p.Hq + (size_t)h * p.G;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    if (!((p.active_mask >> h) & 1ull)) return;   // not covered by this call: rows stay as they are
+    if (s1 <= s0) {   // an item without pages: defined output
+        for (int o = threadIdx.x; o < p.G * FC_D; o += 256) p.out[row * FC_D + o] = 0.f;
+        if (p.lse && threadIdx.x < p.G) p.lse[row + threadIdx.x] = -INFINITY;
+        return;
+    }
+    const int w_first = s0 / L, w_last = (s1 - 1) / L;
+    if (w_first == w_last) return;            // written directly by the attention kernel
+    const int n_parts = w_last - w_first + 1;
+    const int half = lane >> 5, d4 = lane & 31;
+    for (int g = wv; g < p.G; g += 4) {
         float mstar = -INFINITY;
-        for (int w = w_first; w <= w_last; ++w)
-            mstar = fmaxf(mstar, p.part_ml[((size_t)(w + item) * 16 + g) * 2]);
+        for (int i = lane; i < n_parts; i += 64)
+            mstar = fmaxf(mstar, p.part_ml[((size_t)(w_first + i + item) * 16 + g) * 2]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, d));
         float lsum = 0.f;
         float4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-        for (int w = w_first; w <= w_last; ++w) {
-            const size_t slot = (size_t)(w + item);
-            const float wt = __builtin_amdgcn_exp2f(p.part_ml[(slot * 16 + g) * 2] - mstar);
-            lsum += wt * p.part_ml[(slot * 16 + g) * 2 + 1];
-            const float4_t a = *reinterpret_cast<const float4_t *>(p.part_acc + (slot * p.G + g) * FC_D + 4 * d4);
-            acc += wt * a;
+        for (int base = 0; base < n_parts; base += 64) {
+            const int i = base + lane;
+            float wt = 0.f;
+            if (i < n_parts) {
+                const float *ml = p.part_ml + ((size_t)(w_first + i + item) * 16 + g) * 2;
+                wt = __builtin_amdgcn_exp2f(ml[0] - mstar);
+                lsum += wt * ml[1];
+            }
+            const int cnt = min(64, n_parts - base);
+#pragma unroll 8
+            for (int k2 = 0; k2 < cnt; k2 += 2) {          // uniform trip count: shuffles need every lane
+                const int k = k2 + half;
+                const float wk = __shfl(wt, k);               // lanes past the last partial hold 0
+                const size_t slot = (size_t)(w_first + base + min(k, cnt - 1) + item);
+                const float4_t a = *reinterpret_cast<const float4_t *>(p.part_acc + (slot * p.G + g) * FC_D + 4 * d4);
+                acc += wk * a;
+            }
         }
-        const size_t row = (size_t)b * p.Hq + (size_t)h * p.G + g;
-        float4_t r = {0.f, 0.f, 0.f, 0.f};
-        if (w_last >= w_first) r = acc * (1.0f / lsum);
-        *reinterpret_cast<float4_t *>(p.out + row * FC_D + 4 * d4) = r;
-        if (p.lse && d4 == 0)
-            p.lse[row] = w_last >= w_first ? (mstar + __builtin_amdgcn_logf(lsum)) * 0.6931471805599453f : -INFINITY;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) lsum += __shfl_xor(lsum, d);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[v] += __shfl_xor(acc[v], 32);
+        if (half == 0) *reinterpret_cast<float4_t *>(p.out + (row + g) * FC_D + 4 * d4) = acc * (1.0f / lsum);
+        if (p.lse && lane == 0) p.lse[row + g] = (mstar + __builtin_amdgcn_logf(lsum)) * 0.6931471805599453f;
     }
 }
 
@@ -317,6 +358,7 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
                "fc_sparse_decode_attn: NULL pointer among q, kv_pool, block_table, context_lens, stable_flag, out");
     FC_REQUIRE(ctx, a->batch >= 1 && a->batch <= ctx->cfg.max_batch, "fc_sparse_decode_attn: batch=%d outside 1..%d", a->batch, ctx->cfg.max_batch);
     FC_REQUIRE(ctx, a->num_pool_blocks >= 2, "fc_sparse_decode_attn: num_pool_blocks must be >= 2");
+    FC_REQUIRE(ctx, a->head_subset >= FC_HEADS_ALL && a->head_subset <= FC_HEADS_STABLE, "fc_sparse_decode_attn: unknown head_subset %d", a->head_subset);
     const uint64_t mask = fc_stable_mask(ctx->cfg, a->stable_flag);
     FC_REQUIRE(ctx, mask == 0 || (a->topk_pages && a->topk_count), "fc_sparse_decode_attn: stable heads need topk_pages and topk_count");
     hipStream_t s = (hipStream_t)stream;
@@ -330,6 +372,8 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     p.topk_pages = a->topk_pages ? a->topk_pages : a->block_table;   // never read when mask == 0
     p.topk_count = a->topk_count ? a->topk_count : a->context_lens;
     p.stable_mask = mask;
+    const uint64_t all = ctx->cfg.num_kv_heads == 64 ? ~0ull : ((1ull << ctx->cfg.num_kv_heads) - 1);
+    p.active_mask = a->head_subset == FC_HEADS_UNSTABLE ? (all & ~mask) : a->head_subset == FC_HEADS_STABLE ? mask : all;
     p.batch = a->batch;
     p.Hq = ctx->cfg.num_q_heads;
     p.Hkv = ctx->cfg.num_kv_heads;
@@ -339,21 +383,19 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     p.n_waves = ctx->attn_waves;
     p.scale_log2 = ctx->scale_log2;
     p.seg_start = fc_ws_ptr<int32_t>(ctx, ctx->lay.seg_start);
-    p.plan_meta = fc_ws_ptr<int32_t>(ctx, ctx->lay.plan_meta);
-    p.wave_item = fc_ws_ptr<int32_t>(ctx, ctx->lay.wave_item);
     p.part_ml = fc_ws_ptr<float>(ctx, ctx->lay.part_ml);
     p.part_acc = fc_ws_ptr<float>(ctx, ctx->lay.part_acc);
     p.out = a->out;
     p.lse = a->lse;
 
-    if (ctx->copies_pending) {   // promoted pages still in flight on the side stream
+    if (p.active_mask == 0) return FC_OK;
+    if (ctx->copies_pending && (p.active_mask & mask)) {   // promoted pages still in flight on the side stream
         FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_copies_done, 0));
         ctx->copies_pending = false;
     }
-    hipLaunchKernelGGL(fc_attn_plan_kernel, dim3(1), dim3(1024), 0, s, p);
     const bool prof = ctx->profiling && ctx->prof_used < FC_MAX_PROFILE_EVENTS;
     if (prof) FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used], s));
-    hipLaunchKernelGGL(fc_attn_partial_kernel, dim3(p.n_waves / 4), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(fc_decode_attn_kernel, dim3(p.n_waves / 4), dim3(256), 0, s, p);
     if (prof) {
         FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used + 1], s));
         ++ctx->prof_used;

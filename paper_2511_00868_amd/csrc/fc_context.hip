@@ -19,6 +19,7 @@ static int fc_check_config(const fc_config *c, const char **why)
     if (!(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) { *why = "group size must be 1, 2, 4, 8 or 16"; return FC_ERR_UNSUPPORTED; }
     if (c->max_batch < 1 || c->max_batch > (1 << 16)) { *why = "max_batch out of range"; return FC_ERR_INVALID_ARG; }
     if (c->max_pages_per_seq < 1 || c->max_pages_per_seq > (1 << 20)) { *why = "max_pages_per_seq out of range"; return FC_ERR_INVALID_ARG; }
+    if ((long long)c->max_batch * c->num_kv_heads > FC_MAX_ITEMS) { *why = "max_batch * num_kv_heads must be <= 4096"; return FC_ERR_UNSUPPORTED; }
     if (c->max_topk < 1 || c->max_topk > c->max_pages_per_seq) { *why = "max_topk must be in 1..max_pages_per_seq"; return FC_ERR_INVALID_ARG; }
     if (!(c->softmax_scale >= 0.0f) || !isfinite(c->softmax_scale)) { *why = "softmax_scale must be finite and >= 0"; return FC_ERR_INVALID_ARG; }
     if (c->attn_waves < 0 || c->attn_waves > (1 << 16)) { *why = "attn_waves out of range"; return FC_ERR_INVALID_ARG; }
@@ -38,9 +39,7 @@ static void fc_make_layout(const fc_config &c, int attn_waves, fc_ws_layout *l)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = fc_align_up(off + bytes, 256); return o; };
     l->scores = take(items * (size_t)c.max_pages_per_seq * sizeof(float));
-    l->seg_start = take((items + 1) * sizeof(int32_t));
-    l->plan_meta = take(8 * sizeof(int32_t));
-    l->wave_item = take((size_t)attn_waves * sizeof(int32_t));
+    l->seg_start = take((items + 2) * sizeof(int32_t));
     l->part_ml = take(slots * 16 * 2 * sizeof(float));
     l->part_acc = take(slots * (size_t)G * FC_D * sizeof(float));
     l->copy_list = take(items * (size_t)c.max_topk * 2 * sizeof(int32_t));
@@ -143,7 +142,21 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
         delete c;
         return FC_ERR_HIP;
     }
+    // the counter block must start at zero
+    if (hipMemset(c->ws + c->lay.counters, 0, 8 * sizeof(int32_t)) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        (void)hipEventDestroy(c->ev_diff_done);
+        (void)hipEventDestroy(c->ev_copies_done);
+        delete c;
+        return FC_ERR_HIP;
+    }
     c->copies_pending = false;
+    c->promote_calls = 0;
+    c->gather_blocks = 32;   // measured: 16 starves PCIe, 64+ slows a concurrent attention kernel more
+    if (const char *env = getenv("FC_GATHER_BLOCKS")) {
+        const int v = atoi(env);
+        if (v >= 1 && v <= 4096) c->gather_blocks = v;
+    }
     c->err[0] = 0;
     *out = c;
     return FC_OK;
@@ -152,10 +165,10 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
 extern "C" int fc_destroy(fc_ctx *ctx)
 {
     if (!ctx) return FC_ERR_INVALID_ARG;
-    hipEventDestroy(ctx->ev_diff_done);
-    hipEventDestroy(ctx->ev_copies_done);
+    (void)hipEventDestroy(ctx->ev_diff_done);
+    (void)hipEventDestroy(ctx->ev_copies_done);
     for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
-        if (ctx->prof_ev[i]) hipEventDestroy(ctx->prof_ev[i]);
+        if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
     delete ctx;
     return FC_OK;
 }

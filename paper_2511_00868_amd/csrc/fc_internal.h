@@ -15,6 +15,7 @@ constexpr int FC_PAGE_BYTES = FC_PAGE_ELEMS * 2;      // 8192
 constexpr int FC_HALF_BYTES = FC_PAGE_BYTES / 2;      // 4096
 constexpr int FC_MM_ROW_BYTES = 2 * FC_D * 2;         // MinMax bytes per page (512)
 constexpr int FC_MAX_PROFILE_EVENTS = 1024;
+constexpr int FC_MAX_ITEMS = 4096;                   // max_batch * num_kv_heads (schedule lives in LDS)
 
 // Device-side error bits (workspace word `err`).
 constexpr int FC_DEV_ERR_NO_BLOCK = 1;     // a head owned too few blocks for its promoted pages
@@ -24,13 +25,11 @@ constexpr int FC_DEV_ERR_FREE_OVERFLOW = 4;
 // Partition of the caller's device workspace.
 struct fc_ws_layout {
     size_t scores;        // float [max_batch][Hkv][Nmax]
-    size_t seg_start;     // int32 [max_items + 1]
-    size_t plan_meta;     // int32 [8]: 0 = total pages, 1 = pages per wave
-    size_t wave_item;     // int32 [attn_waves]
+    size_t seg_start;     // int32 [max_items + 2]: schedule handed from the attention to the merge kernel
     size_t part_ml;       // float [slots][16][2]  (running max in log2 units, running sum)
     size_t part_acc;      // float [slots][G][128]
     size_t copy_list;     // int32 [max_items * Kmax][2]
-    size_t counters;      // int32 [8]: 0 = copy count, 1 = err
+    size_t counters;      // int32 [8]: 1 = err, 2..3 = copy-pair counts (alternating calls), 4 = recycle workgroups done
     size_t total;
 };
 
@@ -50,6 +49,9 @@ struct fc_ctx {
     hipEvent_t ev_diff_done;
     hipEvent_t ev_copies_done;
     bool copies_pending;
+    unsigned promote_calls;
+    int gather_blocks;    // workgroups of the host->HBM gather kernel: few, the copies are PCIe bound and
+                          // must not crowd the attention kernel off the compute units
     // kernel timing
     bool profiling;
     int prof_used;

@@ -16,8 +16,6 @@
 #include "fc_internal.h"
 
 constexpr int FC_RECYCLE_THREADS = 256;
-constexpr int FC_GATHER_BLOCKS = 64;     // few workgroups: the copies are PCIe bound and must not
-                                         // crowd the attention kernels off the compute units
 
 struct fc_promote_params {
     const int32_t *new_pages;
@@ -34,8 +32,10 @@ struct fc_promote_params {
     uint8_t heads[64];
     long long num_pool_blocks, num_host_blocks;
     int32_t *copy_list;     // device or pinned: pairs (host block, pool block)
-    int32_t *counters;      // device: [0] = pairs appended, [1] = error bits
+    int32_t *counters;      // device: [1] = error bits, [2 + parity] = pairs appended, [4] = workgroups done
+    int parity;             // calls alternate between two pair counters; each call clears the other one
     int32_t *host_total;    // pinned, may be NULL
+    int32_t *host_total2;   // pinned scratch copy (memcpy mode reads it)
     int list_capacity;
 };
 
@@ -69,8 +69,6 @@ __device__ __forceinline__ int fc_block_rank(bool flag, int *wave_cnt, int &tota
     return before + __popcll(bal & ((1ull << lane) - 1ull));
 }
 
-__global__ void fc_zero_counter_kernel(int32_t *counters) { counters[0] = 0; }
-
 __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promote_params p)
 {
     __shared__ int wave_cnt[FC_RECYCLE_THREADS / 64];
@@ -79,11 +77,9 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     const int h = p.heads[blockIdx.x];
     const size_t item = (size_t)b * p.Hkv + h;
     const int tid = threadIdx.x;
-    if (p.rerank_mask && !p.rerank_mask[b]) {
-        if (p.promoted_count && tid == 0) p.promoted_count[item] = 0;
-        return;
-    }
-    int n_old = p.resident_count[item], n_new = p.new_count[item], n_free = p.free_count[item];
+    const bool skip = p.rerank_mask && !p.rerank_mask[b];
+    int n_old = 0, n_new = 0, n_free = 0;
+    if (!skip) { n_old = p.resident_count[item]; n_new = p.new_count[item]; n_free = p.free_count[item]; }
     n_old = min(max(n_old, 0), p.Kmax);
     n_new = min(max(n_new, 0), p.Kmax);
     n_free = min(max(n_free, 0), p.Kmax);
@@ -129,7 +125,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
         fc_block_rank(pr, wave_cnt, tot);
         n_prom += tot;
     }
-    if (tid == 0) sh_list_base = n_prom > 0 ? atomicAdd(&p.counters[0], n_prom) : 0;
+    if (tid == 0) sh_list_base = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
     __syncthreads();
     const int list_base = sh_list_base;
 
@@ -183,28 +179,34 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
         __syncthreads();
     }
     // 5. the new list becomes the resident list
-    for (int i = tid; i < p.Kmax; i += FC_RECYCLE_THREADS) old_l[i] = i < n_new ? new_l[i] : -1;
-    if (tid == 0) {
-        p.free_count[item] = left;
-        p.resident_count[item] = n_new;
-        if (p.promoted_count) p.promoted_count[item] = n_prom;
+    if (!skip) {
+        for (int i = tid; i < p.Kmax; i += FC_RECYCLE_THREADS) old_l[i] = i < n_new ? new_l[i] : -1;
+        if (tid == 0) {
+            p.free_count[item] = left;
+            p.resident_count[item] = n_new;
+        }
     }
+    if (tid == 0 && p.promoted_count) p.promoted_count[item] = n_prom;
     if (err) atomicOr(&p.counters[1], err);
-}
-
-// Publishes the number of pairs where the host can read it (memcpy mode reads it after the event).
-__global__ void fc_publish_total_kernel(const int32_t *counters, int32_t *host_total, int32_t *host_total2)
-{
-    const int v = counters[0];
-    if (host_total) *host_total = v;
-    if (host_total2) *host_total2 = v;
+    // 6. the workgroup that finishes last publishes the pair count and clears the other counter
+    if (tid == 0) {
+        __threadfence();
+        const int done = atomicAdd(&p.counters[4], 1);
+        if (done == (int)(gridDim.x * gridDim.y) - 1) {
+            const int total = atomicAdd(&p.counters[2 + p.parity], 0);
+            if (p.host_total) *p.host_total = total;
+            if (p.host_total2) *p.host_total2 = total;
+            p.counters[2 + (p.parity ^ 1)] = 0;
+            p.counters[4] = 0;
+        }
+    }
 }
 
 __global__ __launch_bounds__(256) void fc_gather_pages_kernel(const int32_t *__restrict__ copy_list,
-                                                              const int32_t *__restrict__ counters, int list_capacity,
+                                                              const int32_t *__restrict__ pair_count, int list_capacity,
                                                               const uint4 *__restrict__ host_pool, uint4 *__restrict__ kv_pool)
 {
-    int total = counters[0];
+    int total = pair_count[0];
     total = total > list_capacity ? list_capacity : total;
     constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
     for (int i = blockIdx.x; i < total; i += gridDim.x) {
@@ -252,19 +254,17 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     p.num_pool_blocks = a->num_pool_blocks;
     p.num_host_blocks = a->num_host_blocks;
     p.counters = fc_ws_ptr<int32_t>(ctx, ctx->lay.counters);
+    p.parity = ctx->promote_calls & 1;
     p.host_total = a->total_promoted;
     p.list_capacity = ctx->max_items * ctx->cfg.max_topk;
     int32_t *scratch_total = reinterpret_cast<int32_t *>(ctx->scratch);
+    p.host_total2 = scratch_total;
     int32_t *scratch_list = reinterpret_cast<int32_t *>(ctx->scratch + 256);
     p.copy_list = a->mode == FC_PROMOTE_GATHER ? fc_ws_ptr<int32_t>(ctx, ctx->lay.copy_list) : scratch_list;
 
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
     if (p.n_stable == 0) {
-        if (a->total_promoted) {
-            hipLaunchKernelGGL(fc_zero_counter_kernel, dim3(1), dim3(1), 0, ms, p.counters);
-            hipLaunchKernelGGL(fc_publish_total_kernel, dim3(1), dim3(1), 0, ms, p.counters, a->total_promoted, (int32_t *)nullptr);
-            FC_HIP(ctx, hipGetLastError());
-        }
+        if (a->total_promoted) *a->total_promoted = 0;
         return FC_OK;
     }
     if (ctx->copies_pending) {
@@ -273,15 +273,14 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
         FC_HIP(ctx, hipStreamWaitEvent(ms, ctx->ev_copies_done, 0));
         ctx->copies_pending = false;
     }
-    hipLaunchKernelGGL(fc_zero_counter_kernel, dim3(1), dim3(1), 0, ms, p.counters);
     hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), 0, ms, p);
-    hipLaunchKernelGGL(fc_publish_total_kernel, dim3(1), dim3(1), 0, ms, p.counters, a->total_promoted, scratch_total);
+    ++ctx->promote_calls;
     FC_HIP(ctx, hipGetLastError());
     FC_HIP(ctx, hipEventRecord(ctx->ev_diff_done, ms));
 
     if (a->mode == FC_PROMOTE_GATHER) {
         FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
-        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(FC_GATHER_BLOCKS), dim3(256), 0, ss, p.copy_list, p.counters,
+        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(256), 0, ss, p.copy_list, p.counters + 2 + p.parity,
                            p.list_capacity, (const uint4 *)a->host_pool, (uint4 *)a->kv_pool);
         FC_HIP(ctx, hipGetLastError());
     } else {

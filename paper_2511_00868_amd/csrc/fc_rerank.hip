@@ -157,15 +157,29 @@ __global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_
                 if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
             }
             __syncthreads();
-            if (tid == 0) {
-                int rem = sh_remaining, d = 255;
-                for (; d > 0; --d) {
-                    const int c = hist[d];
-                    if (c >= rem) break;
-                    rem -= c;
+            // suffix sums over the 256 digit counts by 256 threads: the digit whose suffix sum first
+            // reaches `rem` holds the K-th largest key
+            const int rem = sh_remaining;
+            int c = 0, x = 0;
+            if (tid < 256) {
+                c = hist[255 - tid];
+                x = c;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int y = __shfl_up(x, d);
+                    if (lane >= d) x += y;
                 }
-                sh_remaining = rem;
-                sh_prefix = prefix | ((uint32_t)d << shift);
+                if (lane == 63) wave_cnt[0][wv] = x;
+            }
+            __syncthreads();
+            if (tid < 256) {
+                int incl = x;
+                for (int k = 0; k < wv; ++k) incl += wave_cnt[0][k];
+                const int excl = incl - c;
+                if (incl >= rem && excl < rem) {
+                    sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+                    sh_remaining = rem - excl;
+                }
             }
             mask |= 0xFFu << shift;
             __syncthreads();

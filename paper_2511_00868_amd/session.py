@@ -90,7 +90,8 @@ class DecodeSession:
         self.out = torch.zeros((B, cfg.num_q_heads, 128), dtype=torch.float32, device=self.dev)
         self.lse = torch.zeros((B, cfg.num_q_heads), dtype=torch.float32, device=self.dev)
         self.main = torch.cuda.current_stream(self.dev)
-        self.side = torch.cuda.Stream(self.dev)            # default priority
+        self.copy = torch.cuda.Stream(self.dev)            # host -> HBM page copies (default priority)
+        self.overlap = True
         self.stable = list(cfg.stable)
         for b in range(B):
             self._write_sequence(b, None)
@@ -149,13 +150,13 @@ class DecodeSession:
     def set_queries(self, q_bits: np.ndarray):
         self.q.copy_(self._bits_to_dev(q_bits))
 
-    def rerank(self, rerank_mask=None):
+    def rerank(self, rerank_mask=None, stream=None):
         self.ctx.fc_rerank_topk(q=self.q, minmax=self.minmax, context_lens=self.context_lens,
                                 stable_flag=self.stable, k_per_seq=self.k_per_seq, batch=self.cfg.batch,
                                 topk_pages=self.topk_pages, topk_count=self.topk_count, rerank_mask=rerank_mask,
-                                scores_out=self.scores, stream=self.main)
+                                scores_out=self.scores, stream=stream or self.main)
 
-    def promote(self, rerank_mask=None):
+    def promote(self, rerank_mask=None, stream=None, copy_stream=None):
         self.ctx.fc_promote_pages(new_pages=self.topk_pages, new_count=self.topk_count,
                                   resident_pages=self.resident_pages, resident_count=self.resident_count,
                                   block_table=self.block_table, host_block_table=self.host_block_table,
@@ -163,22 +164,31 @@ class DecodeSession:
                                   stable_flag=self.stable, kv_pool=self.kv_pool,
                                   num_pool_blocks=self.num_pool_blocks, host_pool=self.host_pool,
                                   num_host_blocks=self.num_host_blocks, batch=self.cfg.batch,
-                                  main_stream=self.main, side_stream=self.side, mode=self.promote_mode,
-                                  rerank_mask=rerank_mask, promoted_count=self.promoted_count,
-                                  total_promoted=self.total_promoted)
+                                  main_stream=stream or self.main, side_stream=copy_stream or self.copy,
+                                  mode=self.promote_mode, rerank_mask=rerank_mask,
+                                  promoted_count=self.promoted_count, total_promoted=self.total_promoted)
 
-    def attend(self):
+    def attend(self, head_subset: int = binding.FC_HEADS_ALL):
         self.ctx.fc_sparse_decode_attn(q=self.q, kv_pool=self.kv_pool, num_pool_blocks=self.num_pool_blocks,
                                        block_table=self.block_table, context_lens=self.context_lens,
                                        stable_flag=self.stable, topk_pages=self.resident_pages,
                                        topk_count=self.resident_count, batch=self.cfg.batch, out=self.out,
-                                       lse=self.lse, stream=self.main)
+                                       lse=self.lse, head_subset=head_subset, stream=self.main)
 
     def step(self, t: int):
-        """One pass of the hot path for decode step t (queries already set)."""
+        """One pass of the hot path for decode step t (queries already set on the main stream).
+
+        On a rerank step scoring, selection and block recycling run first; the page copies then go
+        to the copy stream while the main stream attends over the unstable heads, which need none of
+        them; the stable heads follow once the copies have landed (the library makes that call wait,
+        on the GPU, for the copies)."""
         if self.cfg.is_rerank_step(t) and any(self.stable):
             self.rerank()
             self.promote()
+            if self.overlap and not all(self.stable):
+                self.attend(binding.FC_HEADS_UNSTABLE)
+                self.attend(binding.FC_HEADS_STABLE)
+                return
         self.attend()
 
     def selected(self) -> Dict[Tuple[int, int], np.ndarray]:

@@ -68,5 +68,5 @@ def test_create_rejects_null_and_small_buffers():
 def test_struct_sizes_match_the_c_layout():
     assert C.sizeof(binding.fc_config) == 40
     assert C.sizeof(binding.fc_rerank_args) == 80
-    assert C.sizeof(binding.fc_attn_args) == 88
+    assert C.sizeof(binding.fc_attn_args) == 96
     assert C.sizeof(binding.fc_promote_args) == 136
