@@ -178,10 +178,14 @@ int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream
  *   out = softmax(scale * q . K_set^T) V_set   over tokens < context_len, fp32,
  *   lse = natural-log-sum-exp of the scaled logits (optional).
  * Every page of the set must be resident (block_table entry != 0).
- * head_subset restricts the call to one class of heads, leaving the output rows of the other class
- * untouched: a caller that has just promoted pages can run FC_HEADS_UNSTABLE (which does not depend
- * on the copies, and does not wait for them) while they are in flight and FC_HEADS_STABLE afterwards
- * (Sec. 3.3 "Overlapping Transfer with Compute"). */
+ * head_subset splits one attention pass in two so that a caller that has just promoted pages can
+ * overlap the copies with compute (Sec. 3.3 "Overlapping Transfer with Compute"):
+ *   FC_HEADS_UNSTABLE  attends over the unstable heads only; it does not depend on the copies and does
+ *                      not wait for them.  Its output rows are NOT yet written: they become valid with
+ *   FC_HEADS_STABLE    which waits (on the GPU) for the copies, attends over the stable heads and then
+ *                      writes the output rows of both classes (of the stable heads only, if no
+ *                      FC_HEADS_UNSTABLE call preceded it on this context).
+ *   FC_HEADS_ALL       everything in one pass. */
 enum { FC_HEADS_ALL = 0, FC_HEADS_UNSTABLE = 1, FC_HEADS_STABLE = 2 };
 typedef struct {
     const void *q;               /* dev bf16 [batch][num_q_heads][D] */
@@ -204,11 +208,14 @@ int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
  * FC_ERR_STATE. */
 int fc_check_device_state(fc_ctx *ctx, void *stream);
 
-/* Average duration in milliseconds of the dominant kernel (the decode attention kernel)
- * between two calls, measured with HIP events on the stream it was launched on; used by
- * benchmarks.  fc_profile_begin arms it, fc_profile_end synchronises and reports. */
-int fc_profile_begin(fc_ctx *ctx);
-int fc_profile_end(fc_ctx *ctx, double *avg_attn_kernel_ms, int32_t *launches);
+/* Duration of the dominant kernel (the decode attention kernel, FC_HEADS_ALL launches only) measured
+ * with HIP events on the stream it is launched on; used by benchmarks.
+ * fc_profile_begin first measures, on `stream`, what an event pair around an empty kernel reads (the
+ * bracket's own dispatch latency; it synchronises the stream for that), then arms the bracketing of
+ * every `every_nth` (>= 1) such launch.  fc_profile_end synchronises and reports the average raw
+ * bracket time of the attention launches, the average empty-kernel bracket time, and the count. */
+int fc_profile_begin(fc_ctx *ctx, int32_t every_nth, void *stream);
+int fc_profile_end(fc_ctx *ctx, double *avg_bracket_ms, double *empty_bracket_ms, int32_t *launches);
 
 #ifdef __cplusplus
 }

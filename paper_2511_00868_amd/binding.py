@@ -8,7 +8,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libflexicache.so")
+LIB_PATH = os.environ.get("FLEXICACHE_LIB") or os.path.join(HERE, "libflexicache.so")
 
 FC_OK, FC_ERR_INVALID_ARG, FC_ERR_UNSUPPORTED, FC_ERR_WORKSPACE, FC_ERR_HIP, FC_ERR_STATE = 0, -1, -2, -3, -4, -5
 FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY = 0, 1
@@ -79,8 +79,8 @@ def load() -> C.CDLL:
         L.fc_promote_pages.argtypes = [C.c_void_p, C.POINTER(fc_promote_args), C.c_void_p, C.c_void_p]
         L.fc_sparse_decode_attn.argtypes = [C.c_void_p, C.POINTER(fc_attn_args), C.c_void_p]
         L.fc_check_device_state.argtypes = [C.c_void_p, C.c_void_p]
-        L.fc_profile_begin.argtypes = [C.c_void_p]
-        L.fc_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        L.fc_profile_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+        L.fc_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -189,10 +189,11 @@ class Context:
     def fc_check_device_state(self, stream=None):
         self._check(self.lib.fc_check_device_state(self.handle, self._stream(stream)))
 
-    def fc_profile_begin(self):
-        self._check(self.lib.fc_profile_begin(self.handle))
+    def fc_profile_begin(self, every_nth: int = 1, stream=None):
+        self._check(self.lib.fc_profile_begin(self.handle, every_nth, self._stream(stream)))
 
     def fc_profile_end(self):
-        ms, n = C.c_double(), C.c_int32()
-        self._check(self.lib.fc_profile_end(self.handle, C.byref(ms), C.byref(n)))
-        return ms.value, n.value
+        """(average raw bracket ms, empty-kernel bracket ms, launches)"""
+        ms, empty, n = C.c_double(), C.c_double(), C.c_int32()
+        self._check(self.lib.fc_profile_end(self.handle, C.byref(ms), C.byref(empty), C.byref(n)))
+        return ms.value, empty.value, n.value

@@ -23,29 +23,30 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = False) -> str:
-    """Compiles every HIP source and links the shared library; always recompiles."""
+def build(verbose: bool = False, extra_flags=(), out: str = LIB, tag: str = "") -> str:
+    """Compiles every HIP source and links the shared library; always recompiles.  `extra_flags`,
+    `out` and `tag` let tuning experiments build variants (-D overrides) side by side."""
     objs = []
-    build_dir = os.path.join(HERE, "_build")
+    build_dir = os.path.join(HERE, "_build" + tag)
     os.makedirs(build_dir, exist_ok=True)
     procs = []
     for src in SOURCES:
         obj = os.path.join(build_dir, src.replace(".hip", ".o"))
-        cmd = [hipcc(), *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
+        cmd = [hipcc(), *FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
                os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     for src, pr in procs:
-        out, _ = pr.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        log, _ = pr.communicate()
+        log = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l)
         if pr.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{out}")
-        if verbose and out.strip():
-            print(out)
-    tmp = LIB + f".{os.getpid()}.tmp"
+            raise RuntimeError(f"hipcc failed on {src}:\n{log}")
+        if verbose and log.strip():
+            print(log)
+    tmp = out + f".{os.getpid()}.tmp"
     subprocess.check_call([hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
 
 
 if __name__ == "__main__":

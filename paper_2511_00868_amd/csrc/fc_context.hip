@@ -39,9 +39,9 @@ static void fc_make_layout(const fc_config &c, int attn_waves, fc_ws_layout *l)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = fc_align_up(off + bytes, 256); return o; };
     l->scores = take(items * (size_t)c.max_pages_per_seq * sizeof(float));
-    l->seg_start = take((items + 2) * sizeof(int32_t));
-    l->part_ml = take(slots * 16 * 2 * sizeof(float));
-    l->part_acc = take(slots * (size_t)G * FC_D * sizeof(float));
+    l->seg_start = take(2 * (items + 2) * sizeof(int32_t));
+    l->part_ml = take(2 * slots * 16 * 2 * sizeof(float));
+    l->part_acc = take(2 * slots * (size_t)G * FC_D * sizeof(float));
     l->copy_list = take(items * (size_t)c.max_topk * 2 * sizeof(int32_t));
     l->counters = take(8 * sizeof(int32_t));
     l->total = off;
@@ -151,6 +151,7 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
         return FC_ERR_HIP;
     }
     c->copies_pending = false;
+    c->unstable_pending = false;
     c->promote_calls = 0;
     c->gather_blocks = 32;   // measured: 16 starves PCIe, 64+ slows a concurrent attention kernel more
     if (const char *env = getenv("FC_GATHER_BLOCKS")) {
@@ -206,19 +207,39 @@ extern "C" int fc_check_device_state(fc_ctx *ctx, void *stream)
     return FC_OK;
 }
 
-extern "C" int fc_profile_begin(fc_ctx *ctx)
+__global__ void fc_empty_kernel() {}
+
+extern "C" int fc_profile_begin(fc_ctx *ctx, int32_t every_nth, void *stream)
 {
-    if (!ctx) return FC_ERR_INVALID_ARG;
+    if (!ctx || every_nth < 1) return FC_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)stream;
     for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
         if (!ctx->prof_ev[i]) FC_HIP(ctx, hipEventCreate(&ctx->prof_ev[i]));
+    // what the bracket itself costs: event, empty kernel, event
+    constexpr int reps = 32;
+    for (int i = 0; i < reps + 4; ++i) {
+        FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * i], s));
+        hipLaunchKernelGGL(fc_empty_kernel, dim3(1), dim3(64), 0, s);
+        FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * i + 1], s));
+    }
+    FC_HIP(ctx, hipStreamSynchronize(s));
+    double tot = 0.0;
+    for (int i = 4; i < reps + 4; ++i) {   // the first few include one-time launch costs
+        float ms = 0.f;
+        FC_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+        tot += ms;
+    }
+    ctx->prof_empty_ms = tot / reps;
+    ctx->prof_stride = every_nth;
+    ctx->prof_seen = 0;
     ctx->prof_used = 0;
     ctx->profiling = true;
     return FC_OK;
 }
 
-extern "C" int fc_profile_end(fc_ctx *ctx, double *avg_attn_kernel_ms, int32_t *launches)
+extern "C" int fc_profile_end(fc_ctx *ctx, double *avg_bracket_ms, double *empty_bracket_ms, int32_t *launches)
 {
-    if (!ctx || !avg_attn_kernel_ms) return FC_ERR_INVALID_ARG;
+    if (!ctx || !avg_bracket_ms) return FC_ERR_INVALID_ARG;
     ctx->profiling = false;
     double tot = 0.0;
     for (int i = 0; i < ctx->prof_used; ++i) {
@@ -227,7 +248,8 @@ extern "C" int fc_profile_end(fc_ctx *ctx, double *avg_attn_kernel_ms, int32_t *
         FC_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
         tot += ms;
     }
-    *avg_attn_kernel_ms = ctx->prof_used ? tot / ctx->prof_used : 0.0;
+    *avg_bracket_ms = ctx->prof_used ? tot / ctx->prof_used : 0.0;
+    if (empty_bracket_ms) *empty_bracket_ms = ctx->prof_empty_ms;
     if (launches) *launches = ctx->prof_used;
     return FC_OK;
 }

@@ -25,9 +25,9 @@ constexpr int FC_DEV_ERR_FREE_OVERFLOW = 4;
 // Partition of the caller's device workspace.
 struct fc_ws_layout {
     size_t scores;        // float [max_batch][Hkv][Nmax]
-    size_t seg_start;     // int32 [max_items + 2]: schedule handed from the attention to the merge kernel
-    size_t part_ml;       // float [slots][16][2]  (running max in log2 units, running sum)
-    size_t part_acc;      // float [slots][G][128]
+    size_t seg_start;     // int32 [2][max_items + 2]: schedules handed from the attention to the merge kernel
+    size_t part_ml;       // float [2][slots][16][2]  (running max in log2 units, running sum)
+    size_t part_acc;      // float [2][slots][G][128]
     size_t copy_list;     // int32 [max_items * Kmax][2]
     size_t counters;      // int32 [8]: 1 = err, 2..3 = copy-pair counts (alternating calls), 4 = recycle workgroups done
     size_t total;
@@ -49,12 +49,15 @@ struct fc_ctx {
     hipEvent_t ev_diff_done;
     hipEvent_t ev_copies_done;
     bool copies_pending;
+    bool unstable_pending;   // an FC_HEADS_UNSTABLE call has left partials that the next FC_HEADS_STABLE call merges
     unsigned promote_calls;
     int gather_blocks;    // workgroups of the host->HBM gather kernel: few, the copies are PCIe bound and
                           // must not crowd the attention kernel off the compute units
     // kernel timing
     bool profiling;
     int prof_used;
+    int prof_stride, prof_seen;
+    double prof_empty_ms;
     hipEvent_t prof_ev[2 * FC_MAX_PROFILE_EVENTS];
     char err[512];
 };

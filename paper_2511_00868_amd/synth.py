@@ -20,6 +20,8 @@ Recipe
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import Dict, List, Sequence, Tuple
 
@@ -169,20 +171,30 @@ class Workload:
         self.v: List[np.ndarray] = []
         self.hot: Dict[Tuple[int, int], List[int]] = {}
         self._pristine: Dict[Tuple[int, int, int], np.ndarray] = {}
+        def draw(args):
+            b, h, kb, vb, tpad = args
+            g = np.random.default_rng([cfg.seed, 11, b, h])
+            kb[h] = f32_to_bf16_bits(g.standard_normal((tpad, D), dtype=np.float32))
+            vb[h] = f32_to_bf16_bits(g.standard_normal((tpad, D), dtype=np.float32))
+
+        jobs = []
+        for b in range(cfg.batch):
+            tpad = cfg.num_pages(b) * P
+            kb = np.empty((cfg.num_kv_heads, tpad, D), dtype=np.uint16)
+            vb = np.empty((cfg.num_kv_heads, tpad, D), dtype=np.uint16)
+            self.k.append(kb)
+            self.v.append(vb)
+            jobs += [(b, h, kb, vb, tpad) for h in range(cfg.num_kv_heads)]
+        # one independent stream per (sequence, head): the order of drawing does not matter
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            list(ex.map(draw, jobs))
         for b in range(cfg.batch):
             n = cfg.num_pages(b)
             tpad = n * P
-            kb = np.empty((cfg.num_kv_heads, tpad, D), dtype=np.uint16)
-            vb = np.empty((cfg.num_kv_heads, tpad, D), dtype=np.uint16)
-            for h in range(cfg.num_kv_heads):
-                g = np.random.default_rng([cfg.seed, 11, b, h])
-                kb[h] = f32_to_bf16_bits(g.standard_normal((tpad, D), dtype=np.float32))
-                vb[h] = f32_to_bf16_bits(g.standard_normal((tpad, D), dtype=np.float32))
+            kb, vb = self.k[b], self.v[b]
             if cfg.ctx[b] < tpad:
                 kb[:, cfg.ctx[b]:, :] = self.PAD_BITS
                 vb[:, cfg.ctx[b]:, :] = self.PAD_BITS
-            self.k.append(kb)
-            self.v.append(vb)
             nh = hot_per_head_for(cfg, b)
             for h in range(cfg.num_kv_heads):
                 g = np.random.default_rng([cfg.seed, 12, b, h])

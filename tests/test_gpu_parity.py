@@ -68,3 +68,28 @@ def test_all_heads_stable_and_all_heads_unstable():
     base = synth.make_config(2, batch=2, ctx=3000, steps=5)
     _run(dataclasses.replace(base, stable=(True,) * 8, name="all_stable"))
     _run(dataclasses.replace(base, stable=(False,) * 8, dynamics="static", name="all_unstable"))
+
+
+# ---- full benchmark sizes, launch configuration of bench.py, sampled rows ---------------------------
+@pytest.mark.timeout(900)
+def test_config2_full_size_sampled_rows():
+    """Llama-3-8B-shaped layer at 32k context, batch 8: selections, block tables and MinMax are checked
+    for every sequence; attention outputs on two sampled sequences per step."""
+    from parity_util import ParityRun
+    r = ParityRun(synth.make_config(2, steps=6), sample_rows=2, seed=2)
+    try:
+        r.run()
+    finally:
+        r.close()
+
+
+@pytest.mark.timeout(900)
+def test_config3_full_size_128k_sampled_rows():
+    from parity_util import ParityRun
+    r = ParityRun(synth.make_config(3, steps=9), sample_rows=1, seed=3)
+    try:
+        r.check_minmax()
+        for t in (0, 1, 8):      # a cold-fill rerank, a plain step, and the rerank after the drift
+            r.step(t)
+    finally:
+        r.close()
