@@ -313,63 +313,73 @@ __global__ __launch_bounds__(256, 2) void fc_decode_attn_kernel(fc_attn_params p
 }
 
 // ---- merge -----------------------------------------------------------------------------------------
-// One workgroup per item that was split over several wavefronts; wavefront g % 4 combines query g.
-// Lanes first run over the partials (maximum and weights), then over the output: lane = (half, d4)
-// accumulates the partials of its half, weights broadcast by lane shuffle.
+// One workgroup per (split item, query head).  Threads first run over the partials (maximum, then
+// weights into LDS, 256 at a time), then over the output: thread = (sub, d4) accumulates every 8th
+// partial for 4 output dims; the 8 sub-sums are combined through LDS.
 __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
 {
-    const int item = blockIdx.x;
+    __shared__ float wts[256];
+    __shared__ float red[8];
+    __shared__ float4_t accs[8][32];
+    const int item = blockIdx.x, g = blockIdx.y;
     const int items = p.batch * p.Hkv;
     const int b = item / p.Hkv, h = item - b * p.Hkv;
+    if (!((p.active_mask >> h) & 1ull)) return;   // not covered by this call: rows stay as they are
     const int sched = ((p.stable_mask >> h) & 1ull) ? p.sched_stable : p.sched_unstable;
     const int32_t *seg = p.seg_start + (size_t)sched * p.sched_stride;
     const int s0 = seg[item], s1 = seg[item + 1], L = seg[items + 1];
-    const int slot0 = sched * p.slot_stride + item;
-    const size_t row = (size_t)b * p.Hq + (size_t)h * p.G;
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    if (!((p.active_mask >> h) & 1ull)) return;   // not covered by this call: rows stay as they are
+    const size_t row = (size_t)b * p.Hq + (size_t)h * p.G + g;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     if (s1 <= s0) {   // an item without pages: defined output
-        for (int o = threadIdx.x; o < p.G * FC_D; o += 256) p.out[row * FC_D + o] = 0.f;
-        if (p.lse && threadIdx.x < p.G) p.lse[row + threadIdx.x] = -INFINITY;
+        if (tid < FC_D) p.out[row * FC_D + tid] = 0.f;
+        if (p.lse && tid == 0) p.lse[row] = -INFINITY;
         return;
     }
     const int w_first = s0 / L, w_last = (s1 - 1) / L;
     if (w_first == w_last) return;            // written directly by the attention kernel
     const int n_parts = w_last - w_first + 1;
-    const int half = lane >> 5, d4 = lane & 31;
-    for (int g = wv; g < p.G; g += 4) {
-        float mstar = -INFINITY;
-        for (int i = lane; i < n_parts; i += 64)
-            mstar = fmaxf(mstar, p.part_ml[((size_t)(slot0 + w_first + i) * 16 + g) * 2]);
+    const size_t slot0 = (size_t)sched * p.slot_stride + item + w_first;
+
+    float mstar = -INFINITY;
+    for (int i = tid; i < n_parts; i += 256) mstar = fmaxf(mstar, p.part_ml[((slot0 + i) * 16 + g) * 2]);
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, d));
-        float lsum = 0.f;
-        float4_t acc = {0.f, 0.f, 0.f, 0.f};
-        for (int base = 0; base < n_parts; base += 64) {
-            const int i = base + lane;
-            float wt = 0.f;
-            if (i < n_parts) {
-                const float *ml = p.part_ml + ((size_t)(slot0 + w_first + i) * 16 + g) * 2;
-                wt = __builtin_amdgcn_exp2f(ml[0] - mstar);
-                lsum += wt * ml[1];
-            }
-            const int cnt = min(64, n_parts - base);
-#pragma unroll 8
-            for (int k2 = 0; k2 < cnt; k2 += 2) {          // uniform trip count: shuffles need every lane
-                const int k = k2 + half;
-                const float wk = __shfl(wt, k);               // lanes past the last partial hold 0
-                const size_t slot = (size_t)(slot0 + w_first + base + min(k, cnt - 1));
-                const float4_t a = *reinterpret_cast<const float4_t *>(p.part_acc + (slot * p.G + g) * FC_D + 4 * d4);
-                acc += wk * a;
-            }
+    for (int d = 32; d >= 1; d >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, d));
+    if (lane == 0) red[wv] = mstar;
+    __syncthreads();
+    mstar = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+
+    const int sub = tid >> 5, d4 = tid & 31;
+    float lsum = 0.f;
+    float4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int base = 0; base < n_parts; base += 256) {
+        const int cnt = min(256, n_parts - base);
+        if (tid < cnt) {
+            const float *ml = p.part_ml + ((slot0 + base + tid) * 16 + g) * 2;
+            const float wt = __builtin_amdgcn_exp2f(ml[0] - mstar);
+            wts[tid] = wt;
+            lsum += wt * ml[1];
         }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) lsum += __shfl_xor(lsum, d);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) acc[v] += __shfl_xor(acc[v], 32);
-        if (half == 0) *reinterpret_cast<float4_t *>(p.out + (row + g) * FC_D + 4 * d4) = acc * (1.0f / lsum);
-        if (p.lse && lane == 0) p.lse[row + g] = (mstar + __builtin_amdgcn_logf(lsum)) * 0.6931471805599453f;
+        __syncthreads();
+        const float *src = p.part_acc + ((slot0 + base) * p.G + g) * FC_D + 4 * d4;
+#pragma unroll 8
+        for (int k = sub; k < cnt; k += 8)
+            acc += wts[k] * *reinterpret_cast<const float4_t *>(src + (size_t)k * p.G * FC_D);
+        __syncthreads();
     }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) lsum += __shfl_xor(lsum, d);
+    if (lane == 0) red[4 + wv] = lsum;
+    accs[sub][d4] = acc;
+    __syncthreads();
+    lsum = (red[4] + red[5]) + (red[6] + red[7]);
+    if (tid < 32) {
+        float4_t r = accs[0][tid];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) r += accs[k][tid];
+        *reinterpret_cast<float4_t *>(p.out + row * FC_D + 4 * tid) = r * (1.0f / lsum);
+    }
+    if (p.lse && tid == 0) p.lse[row] = (mstar + __builtin_amdgcn_logf(lsum)) * 0.6931471805599453f;
 }
 
 extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *stream)
@@ -442,7 +452,7 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     }
     if (merge_now && merge_mask != 0) {
         p.active_mask = merge_mask;
-        hipLaunchKernelGGL(fc_attn_merge_kernel, dim3(p.batch * p.Hkv), dim3(256), 0, s, p);
+        hipLaunchKernelGGL(fc_attn_merge_kernel, dim3(p.batch * p.Hkv, p.G), dim3(256), 0, s, p);
     }
     FC_HIP(ctx, hipGetLastError());
     return FC_OK;
