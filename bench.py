@@ -130,29 +130,49 @@ def main():
     torch.cuda.synchronize()
     sess.ctx.fc_check_device_state()
 
-    marks = []
+    # ---- timed region: exactly `steps` steps ------------------------------------------------------
     if not args.no_kernel_events:
         sess.ctx.fc_profile_begin(args.kernel_event_stride, main)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(args.warmup, total_steps):
-        run_step(t, marks)
-    e_end = torch.cuda.Event(enable_timing=True)
-    e_end.record(main)
+        run_step(t)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     raw_ms, empty_ms, launches = sess.ctx.fc_profile_end()
     # the bracket's own dispatch latency (measured around an empty kernel in the same run) is not kernel time
     attn_ms = max(raw_ms - empty_ms, 0.0)
     sess.ctx.fc_check_device_state()
+    is_rer_timed = [cfg.is_rerank_step(t) and any(cfg.stable) for t in range(args.warmup, total_steps)]
+
+    # ---- diagnostic pass (untimed for `value`): per-step durations from one event per step ----------
+    diag = min(args.steps, 32)
+    diag = diag - diag % cfg.rerank_interval or diag
+    marks, rr_us, pr_us, cp_us = [], [], [], []
+    names = ("rerank_begin", "rerank_end", "recycle_end", "copies_end")
+    for t in range(diag):
+        tt = t % total_steps
+        rer = cfg.is_rerank_step(tt) and any(cfg.stable)
+        sess.events = {k: torch.cuda.Event(enable_timing=True) for k in names} if rer else None
+        run_step(tt, marks)
+        if rer:
+            ev = sess.events
+            torch.cuda.synchronize()
+            rr_us.append(ev["rerank_begin"].elapsed_time(ev["rerank_end"]) * 1e3)
+            pr_us.append(ev["rerank_end"].elapsed_time(ev["recycle_end"]) * 1e3)
+            cp_us.append(ev["recycle_end"].elapsed_time(ev["copies_end"]) * 1e3)
+    sess.events = None
+    e_end = torch.cuda.Event(enable_timing=True)
+    e_end.record(main)
+    torch.cuda.synchronize()
     marks.append(e_end)
-    step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(args.steps)]
-    is_rer = [cfg.is_rerank_step(t) and any(cfg.stable) for t in range(args.warmup, total_steps)]
+    step_us = [marks[i].elapsed_time(marks[i + 1]) * 1e3 for i in range(diag)]
+    is_rer = [cfg.is_rerank_step(t % total_steps) and any(cfg.stable) for t in range(diag)]
     rer_us = [u for u, r in zip(step_us, is_rer) if r]
     plain_us = [u for u, r in zip(step_us, is_rer) if not r]
     promoted_last = int(sess.total_promoted[0])
 
-    n_rerank = len(rer_us)
+    n_rerank = sum(is_rer_timed)
     a_bytes, r_bytes = attention_bytes(cfg), rerank_bytes(cfg)
     step_bytes = a_bytes * args.steps + r_bytes * n_rerank
     value = step_bytes / elapsed / 1e9
@@ -172,9 +192,15 @@ def main():
         "attn_bytes_per_step": a_bytes, "rerank_bytes_per_invocation": r_bytes,
         "step_us_plain_median": round(float(np.median(plain_us)), 2) if plain_us else None,
         "step_us_rerank_median": round(float(np.median(rer_us)), 2) if rer_us else None,
-        "rerank_exposed_us_per_step_amortised": round((float(np.median(rer_us)) - float(np.median(plain_us))) * n_rerank
-                                                      / args.steps, 2) if rer_us and plain_us else None,
+        "rerank_exposed_us_per_step_amortised": round((float(np.median(rer_us)) - float(np.median(plain_us)))
+                                                      / cfg.rerank_interval, 2) if rer_us and plain_us else None,
+        "attn_call_GBps_plain_step": round(a_bytes / (float(np.median(plain_us)) * 1e-6) / 1e9, 1) if plain_us else None,
+        "rerank_topk_us_per_invocation": round(float(np.median(rr_us)), 2) if rr_us else None,
+        "rerank_topk_us_per_step_amortised": round(float(np.median(rr_us)) / cfg.rerank_interval, 2) if rr_us else None,
+        "recycle_us_per_invocation": round(float(np.median(pr_us)), 2) if pr_us else None,
+        "page_copies_us_per_invocation": round(float(np.median(cp_us)), 2) if cp_us else None,
         "rerank_invocations": n_rerank, "promoted_pages_last_rerank": promoted_last,
+        "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
         "overlap_rerank_with_unstable_heads": sess.overlap,
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",

@@ -157,8 +157,11 @@ __device__ __forceinline__ void fc_store_final(const fc_attn_params &p, size_t r
 
 // SUBSET only names the launch (FC_HEADS_ALL / _UNSTABLE / _STABLE) so that profilers list the three kinds
 // of launch, which move very different numbers of bytes, under separate kernel names.
+#ifndef FC_ATTN_MIN_WAVES_PER_SIMD
+#define FC_ATTN_MIN_WAVES_PER_SIMD 2
+#endif
 template <int SUBSET>
-__global__ __launch_bounds__(256, 2) void fc_decode_attn_kernel(fc_attn_params p)
+__global__ __launch_bounds__(256, FC_ATTN_MIN_WAVES_PER_SIMD) void fc_decode_attn_kernel(fc_attn_params p)
 {
     __shared__ int seg[FC_MAX_ITEMS + 1];     // seg[i] = first page of item i in the concatenated order
     __shared__ int wave_tot[4];

@@ -27,9 +27,11 @@ static int fc_check_config(const fc_config *c, const char **why)
     return FC_OK;
 }
 
-// Wavefronts of the attention kernel when the caller does not choose: a multiple of 4 (one
-// workgroup = 4 wavefronts).  2048 = 256 CUs x 8 on MI355X; used for sizing when no device is asked.
-static int fc_default_waves(int num_cus) { return (num_cus > 0 ? num_cus : 256) * 8; }
+// Wavefronts of the attention kernel when the caller does not choose: one workgroup of 4 wavefronts
+// per compute unit (1024 on MI355X).  Measured on the 32k-context benchmark: 1024 -> 88.7 us, 2048 -> 91.1,
+// 4096 -> 99; counts that are not a multiple of the CU count leave some CUs with twice the work
+// (1536 -> 109 us); 512 leaves half the CUs idle.
+static int fc_default_waves(int num_cus) { return (num_cus > 0 ? num_cus : 256) * 4; }
 
 static void fc_make_layout(const fc_config &c, int attn_waves, fc_ws_layout *l)
 {
@@ -61,8 +63,8 @@ extern "C" size_t fc_workspace_bytes(const fc_config *cfg)
     const char *why;
     if (fc_check_config(cfg, &why) != FC_OK) return 0;
     // Sized for the larger of the default and the requested wave count so that it does not depend
-    // on the device the context is later created on (up to 512 CUs).
-    int waves = fc_resolve_waves(cfg, 512);
+    // on the device the context is later created on (up to 1024 CUs).
+    int waves = fc_resolve_waves(cfg, 1024);
     fc_ws_layout l;
     fc_make_layout(*cfg, waves, &l);
     return l.total;

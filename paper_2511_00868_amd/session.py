@@ -92,6 +92,7 @@ class DecodeSession:
         self.main = torch.cuda.current_stream(self.dev)
         self.copy = torch.cuda.Stream(self.dev)            # host -> HBM page copies (default priority)
         self.overlap = True
+        self.events = None     # optional dict of torch events a benchmark wants recorded on a rerank step
         self.stable = list(cfg.stable)
         for b in range(B):
             self._write_sequence(b, None)
@@ -183,8 +184,16 @@ class DecodeSession:
         them; the stable heads follow once the copies have landed (the library makes that call wait,
         on the GPU, for the copies)."""
         if self.cfg.is_rerank_step(t) and any(self.stable):
+            ev = self.events
+            if ev is not None:
+                ev["rerank_begin"].record(self.main)
             self.rerank()
+            if ev is not None:
+                ev["rerank_end"].record(self.main)
             self.promote()
+            if ev is not None:
+                ev["recycle_end"].record(self.main)
+                ev["copies_end"].record(self.copy)
             if self.overlap and not all(self.stable):
                 self.attend(binding.FC_HEADS_UNSTABLE)
                 self.attend(binding.FC_HEADS_STABLE)
