@@ -19,6 +19,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per whole-pass attention launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same
+# counter reads for a copy kernel of known size (profiles/decode_hot_path_cfg2_llama8b_32k.md)
+MEASURED_TRAFFIC_BYTES = {"cfg2_llama8b_32k": 584.96e6}
 
 
 def attention_bytes(cfg) -> int:
@@ -203,7 +206,7 @@ def main():
         "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
         "overlap_rerank_with_unstable_heads": sess.overlap,
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,
                      "event_bracket_us_raw": round(raw_ms * 1e3, 2), "event_bracket_us_empty_kernel": round(empty_ms * 1e3, 2),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},
