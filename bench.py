@@ -206,7 +206,7 @@ def main():
         "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
         "overlap_rerank_with_unstable_heads": sess.overlap,
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name), "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,
                      "event_bracket_us_raw": round(raw_ms * 1e3, 2), "event_bracket_us_empty_kernel": round(empty_ms * 1e3, 2),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},

@@ -93,3 +93,30 @@ def test_config3_full_size_128k_sampled_rows():
             r.step(t)
     finally:
         r.close()
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size_ragged_batch64_sampled_rows():
+    """64 ragged sequences (4k-32k tokens, partial last pages), blocks shuffled over one shared pool."""
+    from parity_util import ParityRun
+    r = ParityRun(synth.make_config(4, steps=5), sample_rows=3, seed=4)
+    try:
+        r.check_minmax()
+        for t in (0, 1, 4):
+            r.step(t)
+    finally:
+        r.close()
+
+
+@pytest.mark.timeout(900)
+def test_config5_full_size_offload_sampled_rows():
+    """16 x 64k contexts, 5 of 8 heads offloaded: cold fill, then planted pages force promotions."""
+    from parity_util import ParityRun
+    r = ParityRun(synth.make_config(5, steps=9), sample_rows=2, seed=5)
+    try:
+        r.check_minmax()
+        for t in (0, 1, 4, 8):
+            r.step(t)
+        assert r.promoted_total >= 16 * 5 * (256 + 2 * 8)
+    finally:
+        r.close()
