@@ -24,7 +24,7 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {"cfg2_llama8b_32k": 584.96e6}
 
 
-def attention_bytes(cfg) -> int:
+def attention_bytes(cfg, unstable_topk: bool = False) -> int:
     """Algorithmic bytes one fc_sparse_decode_attn call must move: per attended page its valid tokens'
     K and V (512 B per token) and its 4 B table entry (+4 B list entry for a stable head); per
     (sequence, query head) 256 B of query and 512 B of fp32 output."""
@@ -33,7 +33,7 @@ def attention_bytes(cfg) -> int:
         n = cfg.num_pages(b)
         tail = cfg.ctx[b] - 16 * (n - 1)
         for h in range(cfg.num_kv_heads):
-            if cfg.stable[h]:
+            if cfg.stable[h] or unstable_topk:
                 k = min(cfg.topk[b], n)
                 # the partial last page is always a member of a stable head's set
                 toks = 16 * k - ((16 - tail) if tail < 16 else 0)
@@ -44,42 +44,47 @@ def attention_bytes(cfg) -> int:
     return tot
 
 
-def rerank_bytes(cfg) -> int:
+def rerank_bytes(cfg, stable: bool = True) -> int:
     """512 B of MinMax per page of every reranking (sequence, stable head), its queries, 4 B per selected page."""
     tot = 0
     for b in range(cfg.batch):
         n = cfg.num_pages(b)
         for h in range(cfg.num_kv_heads):
-            if cfg.stable[h]:
+            if cfg.stable[h] == stable:
                 tot += 512 * n + cfg.group * 256 + 4 * min(cfg.topk[b], n)
     return tot
 
 
-def cpu_baseline(cfg, wl, budget_s: float = 20.0):
-    """Times the CPU oracle, as it stands, on whole decode steps of the same workload until about
-    `budget_s` seconds of work have been done (at least one step)."""
+def cpu_baseline(cfg, wl, budget_s: float = 15.0, unstable_topk: bool = False):
+    """Times the CPU oracle, as it stands, on whole decode steps of the same workload (step 0, 1, 2, ...
+    with their own queries and the configuration's rerank interval) until `budget_s` seconds of work
+    have been done (at least one step)."""
     import oracle
     dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, cfg.topk,
-                               cfg.rerank_interval)
+                               cfg.rerank_interval, unstable_topk=unstable_topk)
     mm = [oracle.seq_build_minmax(wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]   # untimed: an input
     t0 = time.perf_counter()
     nbytes, steps = 0, 0
     while True:
         q = wl.queries(steps)
+        if unstable_topk:
+            for b in range(cfg.batch):
+                dec.rerank_unstable(b, q[b], mm[b])
+            nbytes += rerank_bytes(cfg, stable=False)
         if cfg.is_rerank_step(steps):
             for b in range(cfg.batch):
                 dec.rerank(b, q[b], mm[b])
             nbytes += rerank_bytes(cfg)
         for b in range(cfg.batch):
             dec.attend(b, q[b], wl.k[b], wl.v[b])
-        nbytes += attention_bytes(cfg)
+        nbytes += attention_bytes(cfg, unstable_topk)
         steps += 1
         el = time.perf_counter() - t0
-        if el > budget_s or steps >= cfg.steps or el * (steps + 1) / steps > 1.5 * budget_s:
+        if el > budget_s:
             break
-    return {"value": nbytes / el / 1e9, "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{steps} whole decode step(s) of {cfg.name} (all {cfg.batch} sequences, rerank on step 0), "
-                      f"{el:.1f} s", "s_per_step": el / steps}
+    return {"value": round(nbytes / el / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{steps} whole decode step(s) of {cfg.name} (all {cfg.batch} sequences, rerank every "
+                      f"{cfg.rerank_interval} steps), {el:.1f} s of oracle time", "s_per_step": round(el / steps, 4)}
 
 
 def main():
@@ -95,8 +100,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-event-stride", type=int, default=4, help="bracket every n-th whole-pass attention launch with HIP events")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket the attention kernel with HIP events")
+    ap.add_argument("--paper-unstable-topk", action="store_true",
+                    help="the paper's own treatment of unstable heads: rescored every step, top-K attention")
     ap.add_argument("--no-overlap", action="store_true", help="run rerank, promotion and attention back to back on one stream")
-    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by sequence or KV head with no "
@@ -112,7 +119,7 @@ def main():
     t_gen = time.perf_counter()
     wl = synth.Workload(cfg)
     mode = binding.FC_PROMOTE_GATHER if args.promote_mode == "gather" else binding.FC_PROMOTE_MEMCPY
-    sess = DecodeSession(cfg, wl, promote_mode=mode, attn_waves=args.attn_waves)
+    sess = DecodeSession(cfg, wl, promote_mode=mode, attn_waves=args.attn_waves, unstable_topk=args.paper_unstable_topk)
     q_all = torch.stack([sess._bits_to_dev(wl.queries(t)) for t in range(total_steps)])
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
@@ -176,8 +183,10 @@ def main():
     promoted_last = int(sess.total_promoted[0])
 
     n_rerank = sum(is_rer_timed)
-    a_bytes, r_bytes = attention_bytes(cfg), rerank_bytes(cfg)
+    a_bytes, r_bytes = attention_bytes(cfg, args.paper_unstable_topk), rerank_bytes(cfg)
     step_bytes = a_bytes * args.steps + r_bytes * n_rerank
+    if args.paper_unstable_topk:
+        step_bytes += rerank_bytes(cfg, stable=False) * args.steps
     value = step_bytes / elapsed / 1e9
     # timed launches are the whole-pass (FC_HEADS_ALL) ones: each moves the full per-step byte count
     bytes_per_launch = a_bytes
@@ -190,7 +199,7 @@ def main():
         "config": {"workload": cfg.name, "batch": cfg.batch, "context": max(cfg.ctx), "q_heads": cfg.num_q_heads,
                    "kv_heads": cfg.num_kv_heads, "stable_heads": int(sum(cfg.stable)), "topk_pages": cfg.max_topk,
                    "rerank_interval": cfg.rerank_interval, "pages_attended_per_step": cfg.pages_attended(),
-                   "promote_mode": args.promote_mode, "attn_wavefronts": sess.ctx.cfg.attn_waves or "auto"},
+                   "promote_mode": args.promote_mode, "unstable_heads": "top-K every step" if args.paper_unstable_topk else "all pages", "attn_wavefronts": sess.ctx.cfg.attn_waves or "auto"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "attn_bytes_per_step": a_bytes, "rerank_bytes_per_invocation": r_bytes,
         "step_us_plain_median": round(float(np.median(plain_us)), 2) if plain_us else None,
@@ -206,14 +215,14 @@ def main():
         "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
         "overlap_rerank_with_unstable_heads": sess.overlap,
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None and not args.paper_unstable_topk else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,
                      "event_bracket_us_raw": round(raw_ms * 1e3, 2), "event_bracket_us_empty_kernel": round(empty_ms * 1e3, 2),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},
         "setup_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_budget)
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_budget, args.paper_unstable_topk)
     sess.close()
     print(json.dumps(out))
 

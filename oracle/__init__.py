@@ -184,15 +184,20 @@ class OracleDecoder:
 
     def __init__(self, batch: int, Hq: int, Hkv: int, ctx: Sequence[int], stable: Sequence[bool],
                  topk: Sequence[int], R: int, D: int = 128, P: int = 16, scale: Optional[float] = None,
-                 group_mode: int = 0):
+                 group_mode: int = 0, unstable_topk: bool = False):
         self.B, self.Hq, self.Hkv, self.D, self.P, self.R = batch, Hq, Hkv, D, P, R
         self.ctx = [int(c) for c in ctx]
         self.stable = [bool(s) for s in stable]
         self.topk = [int(x) for x in topk]
         self.scale = float(scale) if scale else 1.0 / float(np.sqrt(D))
         self.group_mode = group_mode
+        # unstable_topk: the paper's own treatment of unstable heads (Sec. 3.1, 3.2): rescored at every
+        # step, attending over their top-K pages only, everything resident.  Default: they attend over
+        # all pages.
+        self.unstable_topk = unstable_topk
         self.sel: Dict[Tuple[int, int], np.ndarray] = {
-            (b, h): np.empty(0, dtype=np.int32) for b in range(batch) for h in range(Hkv) if self.stable[h]}
+            (b, h): np.empty(0, dtype=np.int32) for b in range(batch) for h in range(Hkv)
+            if self.stable[h] or unstable_topk}
         self.promoted_pages = 0
         self.last_scores: Dict[Tuple[int, int], np.ndarray] = {}
 
@@ -216,11 +221,20 @@ class OracleDecoder:
             res[h] = (promoted, evicted)
         return res
 
+    def rerank_unstable(self, b: int, q_b: np.ndarray, mm_b: np.ndarray) -> None:
+        """Every-step selection of the unstable heads (only meaningful with unstable_topk)."""
+        flags = [not s for s in self.stable]
+        s = seq_scores(q_b, mm_b, flags, self.group_mode)
+        for h in range(self.Hkv):
+            if flags[h]:
+                self.sel[(b, h)] = select_topk(s[h], self.ctx[b], self.topk[b], self.P)
+                self.last_scores[(b, h)] = s[h].copy()
+
     def page_lists(self, b: int, override: Optional[Dict[Tuple[int, int], np.ndarray]] = None
                    ) -> List[np.ndarray]:
         out = []
         for h in range(self.Hkv):
-            if self.stable[h]:
+            if self.stable[h] or self.unstable_topk:
                 src = override if override is not None and (b, h) in override else self.sel
                 out.append(np.asarray(src[(b, h)], dtype=np.int32))
             else:

@@ -55,12 +55,16 @@ def pool_blocks_needed(cfg: DecodeConfig) -> int:
 
 class DecodeSession:
     def __init__(self, cfg: DecodeConfig, wl: Workload, *, device: int = 0, attn_waves: int = 0,
-                 promote_mode: int = binding.FC_PROMOTE_GATHER, keep_scores: bool = False):
+                 promote_mode: int = binding.FC_PROMOTE_GATHER, keep_scores: bool = False,
+                 unstable_topk: bool = False):
         import torch
         self.torch = torch
         self.cfg, self.wl = cfg, wl
         self.dev = torch.device("cuda", device)
         self.promote_mode = promote_mode
+        # the paper's own treatment of unstable heads (Sec. 3.1, 3.2): rescored every step, top-K attention,
+        # all pages resident; their lists are written straight into the resident arrays (nothing to promote)
+        self.unstable_topk = unstable_topk
         B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, min(cfg.max_topk, cfg.max_pages)
         self.ctx = binding.Context(num_q_heads=cfg.num_q_heads, num_kv_heads=H, max_batch=B,
                                    max_pages_per_seq=Nmax, max_topk=Kmax, device=device, attn_waves=attn_waves)
@@ -157,6 +161,14 @@ class DecodeSession:
                                 topk_pages=self.topk_pages, topk_count=self.topk_count, rerank_mask=rerank_mask,
                                 scores_out=self.scores, stream=stream or self.main)
 
+    def rerank_unstable(self):
+        """Paper variant: select the unstable heads' top-K for this step, directly into the lists the
+        attention reads."""
+        self.ctx.fc_rerank_topk(q=self.q, minmax=self.minmax, context_lens=self.context_lens,
+                                stable_flag=[not s for s in self.stable], k_per_seq=self.k_per_seq,
+                                batch=self.cfg.batch, topk_pages=self.resident_pages,
+                                topk_count=self.resident_count, scores_out=self.scores, stream=self.main)
+
     def promote(self, rerank_mask=None, stream=None, copy_stream=None):
         self.ctx.fc_promote_pages(new_pages=self.topk_pages, new_count=self.topk_count,
                                   resident_pages=self.resident_pages, resident_count=self.resident_count,
@@ -170,9 +182,10 @@ class DecodeSession:
                                   promoted_count=self.promoted_count, total_promoted=self.total_promoted)
 
     def attend(self, head_subset: int = binding.FC_HEADS_ALL):
+        listed = [True] * len(self.stable) if self.unstable_topk else self.stable
         self.ctx.fc_sparse_decode_attn(q=self.q, kv_pool=self.kv_pool, num_pool_blocks=self.num_pool_blocks,
                                        block_table=self.block_table, context_lens=self.context_lens,
-                                       stable_flag=self.stable, topk_pages=self.resident_pages,
+                                       stable_flag=listed, topk_pages=self.resident_pages,
                                        topk_count=self.resident_count, batch=self.cfg.batch, out=self.out,
                                        lse=self.lse, head_subset=head_subset, stream=self.main)
 
@@ -183,6 +196,14 @@ class DecodeSession:
         to the copy stream while the main stream attends over the unstable heads, which need none of
         them; the stable heads follow once the copies have landed (the library makes that call wait,
         on the GPU, for the copies)."""
+        if self.unstable_topk:
+            if not all(self.stable):
+                self.rerank_unstable()
+            if self.cfg.is_rerank_step(t) and any(self.stable):
+                self.rerank()
+                self.promote()
+            self.attend()
+            return
         if self.cfg.is_rerank_step(t) and any(self.stable):
             ev = self.events
             if ev is not None:

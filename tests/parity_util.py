@@ -50,12 +50,14 @@ def check_attention(out_gpu: np.ndarray, out_ref: np.ndarray, what: str) -> floa
 
 class ParityRun:
     def __init__(self, cfg: synth.DecodeConfig, *, promote_mode=binding.FC_PROMOTE_GATHER, attn_waves=0,
-                 sample_rows: Optional[int] = None, seed: int = 0):
+                 sample_rows: Optional[int] = None, seed: int = 0, unstable_topk: bool = False):
         self.cfg = cfg
         self.wl = synth.Workload(cfg)
-        self.sess = DecodeSession(cfg, self.wl, promote_mode=promote_mode, attn_waves=attn_waves, keep_scores=True)
+        self.sess = DecodeSession(cfg, self.wl, promote_mode=promote_mode, attn_waves=attn_waves, keep_scores=True,
+                                  unstable_topk=unstable_topk)
+        self.unstable_topk = unstable_topk
         self.dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable,
-                                        cfg.topk, cfg.rerank_interval)
+                                        cfg.topk, cfg.rerank_interval, unstable_topk=unstable_topk)
         self.mm = [oracle.seq_build_minmax(self.wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]
         # oracle-side block bookkeeping, from the same initial placement
         self.o_table = self.sess._bt0.copy()
@@ -90,6 +92,8 @@ class ParityRun:
         sess.ctx.fc_check_device_state()
         rer = cfg.is_rerank_step(t) and any(cfg.stable)
         gpu_sel = sess.selected()
+        if self.unstable_topk and not all(cfg.stable):
+            self.check_unstable_selection(q)
         if rer:
             scores_gpu = sess.scores.cpu().numpy()
             bt_gpu = sess.block_table.cpu().numpy()
@@ -135,6 +139,25 @@ class ParityRun:
             ref, lse = dec.attend(b, q[b], wl.k[b], wl.v[b])
             self.worst = max(self.worst, check_attention(out_gpu[b], ref, f"step {t} seq {b} head "))
             np.testing.assert_allclose(lse_gpu[b], lse, rtol=0, atol=2e-3)
+
+    def check_unstable_selection(self, q):
+        """Paper variant: the unstable heads' every-step top-K against the oracle's (near-tie audited)."""
+        cfg, sess, dec = self.cfg, self.sess, self.dec
+        pages = sess.resident_pages.cpu().numpy()
+        cnt = sess.resident_count.cpu().numpy()
+        for b in range(cfg.batch):
+            n = cfg.num_pages(b)
+            forced = n - 1 if cfg.ctx[b] % 16 else -1
+            dec.rerank_unstable(b, q[b], self.mm[b])
+            for h in range(cfg.num_kv_heads):
+                if cfg.stable[h]:
+                    continue
+                g = pages[b, h, :cnt[b, h]]
+                assert np.all(np.diff(g) > 0)
+                audit_sets(g, dec.sel[(b, h)], dec.last_scores[(b, h)], forced)
+                if set(g) != set(dec.sel[(b, h)]):
+                    self.near_tie_swaps += 1
+                    dec.sel[(b, h)] = np.array(sorted(g), dtype=np.int32)
 
     def check_resident_pages(self, bt_gpu, max_pages: int = 200):
         """Every resident page of a stable head holds exactly the bytes of that page (native layout)."""

@@ -120,3 +120,19 @@ def test_config5_full_size_offload_sampled_rows():
         assert r.promoted_total >= 16 * 5 * (256 + 2 * 8)
     finally:
         r.close()
+
+
+# ---- the paper's own treatment of unstable heads: top-K attention, rescored at every step -----------
+def test_paper_variant_unstable_heads_topk_every_step_reduced():
+    _run(synth.make_config(2, batch=3, ctx=4096 + 7, steps=6), unstable_topk=True)
+    _run(synth.make_config(4, batch=5, ctx=5000, steps=5), unstable_topk=True)
+
+
+@pytest.mark.timeout(900)
+def test_paper_variant_full_size_sampled_rows():
+    from parity_util import ParityRun
+    r = ParityRun(synth.make_config(2, steps=5), sample_rows=2, seed=6, unstable_topk=True)
+    try:
+        r.run()
+    finally:
+        r.close()

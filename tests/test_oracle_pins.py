@@ -305,3 +305,28 @@ def test_sparse_attention_of_stable_head_is_close_to_dense_when_hot_pages_domina
     q = w.queries(0)[0]
     ref, _ = dense_attention_numpy(q[0], w.k[0][0], w.v[0][0], cfg.ctx[0], 1 / np.sqrt(128))
     assert np.abs(outs[0][0] - ref).max() < 0.5
+
+
+def test_paper_variant_of_unstable_heads_selects_per_step_and_reduces_to_dense_with_full_budget():
+    cfg = synth.make_config(1)
+    w = synth.Workload(cfg)
+    mm = oracle.seq_build_minmax(w.k[0], cfg.ctx[0])
+    dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, [128], 2,
+                               unstable_topk=True)
+    q = w.queries(0)[0]
+    dec.rerank(0, q, mm)
+    dec.rerank_unstable(0, q, mm)
+    assert len(dec.sel[(0, 1)]) == 128                      # head 1 is the unstable one
+    out, _ = dec.attend(0, q, w.k[0], w.v[0])
+    for hq in range(cfg.num_q_heads):
+        h = hq // cfg.group
+        ref, _ = dense_attention_numpy(q[hq], w.k[0][h], w.v[0][h], cfg.ctx[0], 1 / np.sqrt(128))
+        np.testing.assert_allclose(out[hq], ref, rtol=1e-12, atol=1e-13)
+    # with a real budget the unstable head follows the query of the step
+    dec8 = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, [8], 2,
+                                unstable_topk=True)
+    for t in range(2):
+        qt = w.queries(t)[0]
+        dec8.rerank_unstable(0, qt, mm)
+        s = oracle.page_scores(qt[cfg.group:2 * cfg.group], mm[1])
+        np.testing.assert_array_equal(dec8.sel[(0, 1)], oracle.select_topk(s, cfg.ctx[0], 8))
