@@ -200,8 +200,16 @@ class DecodeSession:
             if not all(self.stable):
                 self.rerank_unstable()
             if self.cfg.is_rerank_step(t) and any(self.stable):
+                ev = self.events
+                if ev is not None:
+                    ev["rerank_begin"].record(self.main)
                 self.rerank()
+                if ev is not None:
+                    ev["rerank_end"].record(self.main)
                 self.promote()
+                if ev is not None:
+                    ev["recycle_end"].record(self.main)
+                    ev["copies_end"].record(self.copy)
             self.attend()
             return
         if self.cfg.is_rerank_step(t) and any(self.stable):
