@@ -203,6 +203,49 @@ typedef struct {
 } fc_attn_args;
 int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
 
+/* ---- decode-time growth of the cache ------------------------------------------------------------- */
+
+/* Appends one new token per sequence (Sec. 2: decoding appends one K/V pair per step) and keeps the
+ * derived state current.  For every sequence b with append_mask[b] != 0 and every KV head h, with
+ * pos = context_lens[b], page = pos / 16, slot = pos % 16:
+ *   - slot == 0: a new page starts.  It takes the LAST block of the head's free list (free_count
+ *     decreases by one) and block_table[b][h][page] is set; for a stable head the page also joins
+ *     resident_pages (it is being appended to, so it is always a member, Sec. 3.3);
+ *   - the token's key goes to row `slot` of the K half and its value to column `slot` of the V half;
+ *   - MinMax row of the page (Sec. 3.2): set to the key when slot == 0, else elementwise min / max;
+ *   - slot == 15 and the head is stable: the page is now full and is copied, once, to
+ *     host_pool[host_block_table[b][h][page]] (Sec. 3.3 "Minimizing Transfer Size"); it stays resident
+ *     until a later rerank evicts it.
+ * Afterwards context_lens[b] += 1.  Needs: page < Nmax, a free block when a page starts, room in the
+ * resident list (Kmax > budget + pages started between two reranks); violations set the device error
+ * word (fc_check_device_state) and leave that head's state untouched. */
+typedef struct {
+    const void *k_new;               /* dev bf16 [batch][num_kv_heads][D] */
+    const void *v_new;               /* dev bf16 [batch][num_kv_heads][D] */
+    const uint8_t *append_mask;      /* dev [batch] or NULL (= every sequence) */
+    int32_t *context_lens;           /* dev in/out [batch] */
+    int32_t *block_table;            /* dev in/out */
+    const int32_t *host_block_table; /* dev (stable heads) */
+    int32_t *free_blocks;            /* dev in/out [batch][num_kv_heads][Kmax] */
+    int32_t *free_count;             /* dev in/out [batch][num_kv_heads] */
+    int32_t *resident_pages;         /* dev in/out (stable heads) */
+    int32_t *resident_count;         /* dev in/out (stable heads) */
+    void *minmax;                    /* dev in/out bf16 [batch][num_kv_heads][Nmax][2][D] */
+    void *kv_pool;                   /* dev */
+    int64_t num_pool_blocks;
+    void *host_pool;                 /* pinned (stable heads) */
+    int64_t num_host_blocks;
+    const uint8_t *stable_flag;      /* host [num_kv_heads] */
+    int32_t batch;
+} fc_append_args;
+int fc_append_kv(fc_ctx *ctx, const fc_append_args *args, void *stream);
+
+/* Bulk HBM -> pinned host copy of whole pages (the offload after prefill, Sec. 3.3 "Overlapping
+ * Transfer with Compute"): pairs[i] = (pool block, host block), dev int32 [n_pairs][2].  A capped
+ * number of workgroups writes pinned host memory directly; pairs outside either pool are skipped. */
+int fc_offload_pages(fc_ctx *ctx, const void *kv_pool, int64_t num_pool_blocks, void *host_pool,
+                     int64_t num_host_blocks, const int32_t *pairs, int32_t n_pairs, void *stream);
+
 /* Reads (and clears) the device-side error word set by the bookkeeping kernels (a head owning too
  * few blocks, an id out of range that was clamped).  Synchronises `stream`.  Returns FC_OK or
  * FC_ERR_STATE. */

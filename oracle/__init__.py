@@ -221,6 +221,20 @@ class OracleDecoder:
             res[h] = (promoted, evicted)
         return res
 
+    def append(self, b: int) -> Optional[int]:
+        """One token joins sequence b (Sec. 2).  If it starts a new page, that page -- partially filled,
+        being appended to -- joins the selection of every head that attends over a list (Sec. 3.3).
+        Returns the index of the page that was started, or None."""
+        pos = self.ctx[b]
+        self.ctx[b] = pos + 1
+        if pos % self.P != 0:
+            return None
+        page = pos // self.P
+        for h in range(self.Hkv):
+            if (b, h) in self.sel and self.stable[h]:
+                self.sel[(b, h)] = np.append(self.sel[(b, h)], np.int32(page)).astype(np.int32)
+        return page
+
     def rerank_unstable(self, b: int, q_b: np.ndarray, mm_b: np.ndarray) -> None:
         """Every-step selection of the unstable heads (only meaningful with unstable_topk)."""
         flags = [not s for s in self.stable]

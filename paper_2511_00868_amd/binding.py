@@ -14,9 +14,18 @@ FC_OK, FC_ERR_INVALID_ARG, FC_ERR_UNSUPPORTED, FC_ERR_WORKSPACE, FC_ERR_HIP, FC_
 FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY = 0, 1
 FC_HEADS_ALL, FC_HEADS_UNSTABLE, FC_HEADS_STABLE = 0, 1, 2
 
+class fc_append_args(C.Structure):
+    _fields_ = [("k_new", C.c_void_p), ("v_new", C.c_void_p), ("append_mask", C.c_void_p),
+                ("context_lens", C.c_void_p), ("block_table", C.c_void_p), ("host_block_table", C.c_void_p),
+                ("free_blocks", C.c_void_p), ("free_count", C.c_void_p), ("resident_pages", C.c_void_p),
+                ("resident_count", C.c_void_p), ("minmax", C.c_void_p), ("kv_pool", C.c_void_p),
+                ("num_pool_blocks", C.c_int64), ("host_pool", C.c_void_p), ("num_host_blocks", C.c_int64),
+                ("stable_flag", C.c_void_p), ("batch", C.c_int32)]
+
+
 EXPORTS = ["fc_workspace_bytes", "fc_host_scratch_bytes", "fc_create", "fc_destroy", "fc_status_string",
            "fc_last_error", "fc_write_kv_pages", "fc_build_minmax", "fc_rerank_topk", "fc_promote_pages",
-           "fc_sparse_decode_attn", "fc_check_device_state", "fc_profile_begin", "fc_profile_end"]
+           "fc_sparse_decode_attn", "fc_append_kv", "fc_offload_pages", "fc_check_device_state", "fc_profile_begin", "fc_profile_end"]
 
 
 class fc_config(C.Structure):
@@ -78,6 +87,9 @@ def load() -> C.CDLL:
         L.fc_rerank_topk.argtypes = [C.c_void_p, C.POINTER(fc_rerank_args), C.c_void_p]
         L.fc_promote_pages.argtypes = [C.c_void_p, C.POINTER(fc_promote_args), C.c_void_p, C.c_void_p]
         L.fc_sparse_decode_attn.argtypes = [C.c_void_p, C.POINTER(fc_attn_args), C.c_void_p]
+        L.fc_append_kv.argtypes = [C.c_void_p, C.POINTER(fc_append_args), C.c_void_p]
+        L.fc_offload_pages.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
+                                       C.c_void_p]
         L.fc_check_device_state.argtypes = [C.c_void_p, C.c_void_p]
         L.fc_profile_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.fc_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
@@ -185,6 +197,21 @@ class Context:
         a = fc_attn_args(_ptr(q), _ptr(kv_pool), num_pool_blocks, _ptr(block_table), _ptr(context_lens),
                          C.addressof(flags), _ptr(topk_pages), _ptr(topk_count), batch, _ptr(out), _ptr(lse), head_subset)
         self._check(self.lib.fc_sparse_decode_attn(self.handle, C.byref(a), self._stream(stream)))
+
+    def fc_append_kv(self, *, k_new, v_new, context_lens, block_table, host_block_table, free_blocks, free_count,
+                     resident_pages, resident_count, minmax, kv_pool, num_pool_blocks: int, host_pool,
+                     num_host_blocks: int, stable_flag, batch: int, append_mask=None, stream=None):
+        flags = _host_u8(stable_flag)
+        a = fc_append_args(_ptr(k_new), _ptr(v_new), _ptr(append_mask), _ptr(context_lens), _ptr(block_table),
+                           _ptr(host_block_table), _ptr(free_blocks), _ptr(free_count), _ptr(resident_pages),
+                           _ptr(resident_count), _ptr(minmax), _ptr(kv_pool), num_pool_blocks, _ptr(host_pool),
+                           num_host_blocks, C.addressof(flags), batch)
+        self._check(self.lib.fc_append_kv(self.handle, C.byref(a), self._stream(stream)))
+
+    def fc_offload_pages(self, kv_pool, num_pool_blocks: int, host_pool, num_host_blocks: int, pairs, n_pairs: int,
+                         stream=None):
+        self._check(self.lib.fc_offload_pages(self.handle, _ptr(kv_pool), num_pool_blocks, _ptr(host_pool),
+                                              num_host_blocks, _ptr(pairs), n_pairs, self._stream(stream)))
 
     def fc_check_device_state(self, stream=None):
         self._check(self.lib.fc_check_device_state(self.handle, self._stream(stream)))

@@ -29,7 +29,7 @@ struct fc_ws_layout {
     size_t part_ml;       // float [2][slots][16][2]  (running max in log2 units, running sum)
     size_t part_acc;      // float [2][slots][G][128]
     size_t copy_list;     // int32 [max_items * Kmax][2]
-    size_t counters;      // int32 [8]: 1 = err, 2..3 = copy-pair counts (alternating calls), 4 = recycle workgroups done
+    size_t counters;      // int32 [8]: 1 = err, 2..3 = copy-pair counts (alternating calls), 4 = recycle workgroups done, 5 = append workgroups done
     size_t total;
 };
 

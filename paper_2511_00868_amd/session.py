@@ -22,34 +22,45 @@ def plan_placement(cfg: DecodeConfig, block_order: np.ndarray):
     blocks (its slots, all free at the start) and one host block per page.  Returns
     (block_table [B,Hkv,Nmax], host_block_table, free_blocks [B,Hkv,Kmax], free_count [B,Hkv],
     num_pool_blocks, num_host_blocks).  Block 0 of either pool is never handed out."""
-    B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, min(cfg.max_topk, cfg.max_pages)
+    B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, list_capacity(cfg)
     bt = np.zeros((B, H, Nmax), dtype=np.int32)
     hbt = np.zeros((B, H, Nmax), dtype=np.int32)
     fb = np.zeros((B, H, Kmax), dtype=np.int32)
     fc = np.zeros((B, H), dtype=np.int32)
     nxt, hnxt = 0, 1
     for b in range(B):
-        n = cfg.num_pages(b)
+        n, nf = cfg.num_pages(b), cfg.final_pages(b)
+        grow = nf - n                      # pages that will be started by appended tokens
         for h in range(H):
             if cfg.stable[h]:
-                k = min(cfg.topk[b], n)
+                k = min(cfg.topk[b], n) + grow
                 fb[b, h, :k] = block_order[nxt:nxt + k]
                 fc[b, h] = k
                 nxt += k
-                hbt[b, h, :n] = np.arange(hnxt, hnxt + n)
-                hnxt += n
+                hbt[b, h, :nf] = np.arange(hnxt, hnxt + nf)
+                hnxt += nf
             else:
                 bt[b, h, :n] = block_order[nxt:nxt + n]
                 nxt += n
+                fb[b, h, :grow] = block_order[nxt:nxt + grow]
+                fc[b, h] = grow
+                nxt += grow
     return bt, hbt, fb, fc, nxt + 1, hnxt
+
+
+def list_capacity(cfg: DecodeConfig) -> int:
+    """Kmax: entries of a page list / free list: the budget plus the pages appended tokens can start
+    between two reranks (they join the resident list at once and leave it at the next rerank)."""
+    cur = max(cfg.num_pages(b) for b in range(cfg.batch))
+    return min(cfg.max_topk, cur) + cfg.growth_pages + (1 if cfg.append_tokens else 0)
 
 
 def pool_blocks_needed(cfg: DecodeConfig) -> int:
     tot = 0
     for b in range(cfg.batch):
-        n = cfg.num_pages(b)
+        n, grow = cfg.num_pages(b), cfg.final_pages(b) - cfg.num_pages(b)
         for h in range(cfg.num_kv_heads):
-            tot += min(cfg.topk[b], n) if cfg.stable[h] else n
+            tot += (min(cfg.topk[b], n) if cfg.stable[h] else n) + grow
     return tot
 
 
@@ -65,7 +76,7 @@ class DecodeSession:
         # the paper's own treatment of unstable heads (Sec. 3.1, 3.2): rescored every step, top-K attention,
         # all pages resident; their lists are written straight into the resident arrays (nothing to promote)
         self.unstable_topk = unstable_topk
-        B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, min(cfg.max_topk, cfg.max_pages)
+        B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, list_capacity(cfg)
         self.ctx = binding.Context(num_q_heads=cfg.num_q_heads, num_kv_heads=H, max_batch=B,
                                    max_pages_per_seq=Nmax, max_topk=Kmax, device=device, attn_waves=attn_waves)
         order = wl.block_permutation(pool_blocks_needed(cfg))
@@ -109,15 +120,18 @@ class DecodeSession:
     def _write_sequence(self, b: int, only: Optional[Dict[int, Sequence[int]]]):
         """(Re)writes pages of sequence b from the master copy: `only` = {head: pages} or None = all."""
         torch, cfg = self.torch, self.cfg
-        n = cfg.num_pages(b)
-        kd, vd = self._bits_to_dev(self.wl.k[b]), self._bits_to_dev(self.wl.v[b])
+        cur = self.wl.cur_len[b]
+        n = -(-cur // 16)
+        kd = self._bits_to_dev(np.ascontiguousarray(self.wl.k[b][:, :n * 16]))
+        vd = self._bits_to_dev(np.ascontiguousarray(self.wl.v[b][:, :n * 16]))
         sel = np.zeros((cfg.num_kv_heads, n), dtype=bool)
         if only is None:
             sel[:] = True
         else:
             for h, pages in only.items():
                 sel[h, list(pages)] = True
-        hbm_ids = np.where(sel, self._current_table(b)[:, :n], 0).astype(np.int32)
+        table_now = self._current_table(b)
+        hbm_ids = np.where(sel, table_now[:, :n], 0).astype(np.int32)
         host_ids = np.where(sel, self._hbt[b][:, :n], 0).astype(np.int32)
         hbm_ids_d = torch.from_numpy(np.ascontiguousarray(hbm_ids)).to(self.dev)
         host_ids_d = torch.from_numpy(np.ascontiguousarray(host_ids)).to(self.dev)
@@ -131,12 +145,12 @@ class DecodeSession:
         else:
             pages = sorted({p for ps in only.values() for p in ps})
             plist, nl = torch.tensor(pages, dtype=torch.int32, device=self.dev), len(pages)
-        unst = np.where(np.array(self.stable)[:, None], 0, self._bt0[b][:, :n]).astype(np.int32)
+        unst = np.where(np.array(self.stable)[:, None], 0, table_now[:, :n]).astype(np.int32)
         c.fc_build_minmax(self.kv_pool, self.num_pool_blocks, torch.from_numpy(np.ascontiguousarray(unst)).to(self.dev),
-                          plist, nl, cfg.ctx[b], self.minmax[b], self.main)
+                          plist, nl, cur, self.minmax[b], self.main)
         if any(self.stable):
             hst = torch.from_numpy(np.ascontiguousarray(self._hbt[b][:, :n])).to(self.dev)
-            c.fc_build_minmax(self.host_pool, self.num_host_blocks, hst, plist, nl, cfg.ctx[b], self.minmax[b],
+            c.fc_build_minmax(self.host_pool, self.num_host_blocks, hst, plist, nl, cur, self.minmax[b],
                               self.main)
         torch.cuda.synchronize(self.dev)   # kd / vd die with this frame
 
@@ -154,6 +168,18 @@ class DecodeSession:
     # ---- the three hot-path calls -------------------------------------------------------------------
     def set_queries(self, q_bits: np.ndarray):
         self.q.copy_(self._bits_to_dev(q_bits))
+
+    def append(self, k_bits: np.ndarray, v_bits: np.ndarray, append_mask=None):
+        """One new token per sequence: page write, MinMax update, offload of pages that fill (library)."""
+        kd, vd = self._bits_to_dev(k_bits), self._bits_to_dev(v_bits)
+        self.ctx.fc_append_kv(k_new=kd, v_new=vd, context_lens=self.context_lens, block_table=self.block_table,
+                              host_block_table=self.host_block_table, free_blocks=self.free_blocks,
+                              free_count=self.free_count, resident_pages=self.resident_pages,
+                              resident_count=self.resident_count, minmax=self.minmax, kv_pool=self.kv_pool,
+                              num_pool_blocks=self.num_pool_blocks, host_pool=self.host_pool,
+                              num_host_blocks=self.num_host_blocks, stable_flag=self.stable,
+                              batch=self.cfg.batch, append_mask=append_mask, stream=self.main)
+        self.torch.cuda.current_stream(self.dev).synchronize()   # kd / vd die with this frame
 
     def rerank(self, rerank_mask=None, stream=None):
         self.ctx.fc_rerank_topk(q=self.q, minmax=self.minmax, context_lens=self.context_lens,

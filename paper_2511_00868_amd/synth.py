@@ -63,6 +63,7 @@ class DecodeConfig:
     dynamics: str              # "static" | "unstable_resample" | "drift" | "plant_nonresident"
     dynamics_pages: int = 0    # pages changed per event for drift / plant_nonresident
     shuffle_blocks: bool = False
+    append_tokens: int = 0     # tokens appended to every sequence during the run (one per step), 0 = fixed context
     head_dim: int = 128
     page_size: int = 16
     seed: int = 0
@@ -74,9 +75,17 @@ class DecodeConfig:
     def num_pages(self, b: int) -> int:
         return -(-self.ctx[b] // self.page_size)
 
+    def final_pages(self, b: int) -> int:
+        """Pages of sequence b once every appended token is in."""
+        return -(-(self.ctx[b] + self.append_tokens) // self.page_size)
+
     @property
     def max_pages(self) -> int:
-        return max(self.num_pages(b) for b in range(self.batch))
+        return max(self.final_pages(b) for b in range(self.batch))
+
+    @property
+    def growth_pages(self) -> int:
+        return max(self.final_pages(b) - self.num_pages(b) for b in range(self.batch))
 
     @property
     def max_topk(self) -> int:
@@ -177,9 +186,10 @@ class Workload:
             kb[h] = f32_to_bf16_bits(g.standard_normal((tpad, D), dtype=np.float32))
             vb[h] = f32_to_bf16_bits(g.standard_normal((tpad, D), dtype=np.float32))
 
+        self.cur_len = list(cfg.ctx)     # grows with append()
         jobs = []
         for b in range(cfg.batch):
-            tpad = cfg.num_pages(b) * P
+            tpad = cfg.final_pages(b) * P
             kb = np.empty((cfg.num_kv_heads, tpad, D), dtype=np.uint16)
             vb = np.empty((cfg.num_kv_heads, tpad, D), dtype=np.uint16)
             self.k.append(kb)
@@ -190,7 +200,7 @@ class Workload:
             list(ex.map(draw, jobs))
         for b in range(cfg.batch):
             n = cfg.num_pages(b)
-            tpad = n * P
+            tpad = cfg.final_pages(b) * P
             kb, vb = self.k[b], self.v[b]
             if cfg.ctx[b] < tpad:
                 kb[:, cfg.ctx[b]:, :] = self.PAD_BITS
@@ -205,7 +215,7 @@ class Workload:
     # ---- hot pages -----------------------------------------------------------------------------
     def _page_slice(self, b: int, p: int) -> slice:
         P = self.cfg.page_size
-        return slice(p * P, min((p + 1) * P, self.cfg.ctx[b]))
+        return slice(p * P, min((p + 1) * P, self.cur_len[b]))
 
     def _plant(self, b: int, h: int, pages: Sequence[int]) -> None:
         for p in pages:
@@ -236,7 +246,7 @@ class Workload:
         if t <= 0 or cfg.dynamics == "static":
             return changed
         for b in range(cfg.batch):
-            n = cfg.num_pages(b)
+            n = -(-self.cur_len[b] // cfg.page_size)
             for h in range(cfg.num_kv_heads):
                 g = np.random.default_rng([cfg.seed, 13, b, h, t])
                 cur = self.hot[(b, h)]
@@ -262,6 +272,24 @@ class Workload:
                     self._plant(b, h, new)
                     changed.append((b, h, sorted(set(old) | set(new))))
         return changed
+
+    # ---- appended tokens -----------------------------------------------------------------------
+    def append(self, t: int) -> Tuple[np.ndarray, np.ndarray]:
+        """Draws the token every sequence appends before decode step t, stores it in the master copy
+        and returns its (k, v) bit patterns, each [B, Hkv, D]."""
+        cfg = self.cfg
+        k = np.empty((cfg.batch, cfg.num_kv_heads, cfg.head_dim), dtype=np.uint16)
+        v = np.empty_like(k)
+        for b in range(cfg.batch):
+            g = np.random.default_rng([cfg.seed, 16, b, t])
+            k[b] = f32_to_bf16_bits(g.standard_normal((cfg.num_kv_heads, cfg.head_dim), dtype=np.float32))
+            v[b] = f32_to_bf16_bits(g.standard_normal((cfg.num_kv_heads, cfg.head_dim), dtype=np.float32))
+            pos = self.cur_len[b]
+            assert pos < self.k[b].shape[1], "more tokens appended than the configuration announced"
+            self.k[b][:, pos, :] = k[b]
+            self.v[b][:, pos, :] = v[b]
+            self.cur_len[b] = pos + 1
+        return k, v
 
     # ---- queries -------------------------------------------------------------------------------
     def queries(self, t: int) -> np.ndarray:

@@ -59,32 +59,87 @@ class ParityRun:
         self.dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable,
                                         cfg.topk, cfg.rerank_interval, unstable_topk=unstable_topk)
         self.mm = [oracle.seq_build_minmax(self.wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]
+        self.appended_pages = []          # (b, page) pages started by appended tokens
         # oracle-side block bookkeeping, from the same initial placement
         self.o_table = self.sess._bt0.copy()
         fb = self.sess.free_blocks.cpu().numpy()
         fc = self.sess.free_count.cpu().numpy()
         self.o_free = {(b, h): [int(x) for x in fb[b, h, :fc[b, h]]] for b in range(cfg.batch)
-                       for h in range(cfg.num_kv_heads) if cfg.stable[h]}
+                       for h in range(cfg.num_kv_heads)}
         self.sample_rows = sample_rows
         self.rng = np.random.default_rng(seed)
         self.worst = 0.0
         self.near_tie_swaps = 0
         self.promoted_total = 0
 
+    def pages_now(self, b: int) -> int:
+        return -(-self.wl.cur_len[b] // 16)
+
     def check_minmax(self):
         mm_gpu = self.sess.minmax.cpu().view(self.sess.torch.int16).numpy().view(np.uint16)
         for b in range(self.cfg.batch):
-            n = self.cfg.num_pages(b)
+            n = self.pages_now(b)
             np.testing.assert_array_equal(widen(mm_gpu[b, :, :n]), widen(self.mm[b]))
+
+    def append_token(self, t: int):
+        """Both sides append the token of step t; tables, free lists, MinMax rows, page bytes and the
+        host copy of pages that just filled are compared."""
+        cfg, wl, sess, dec = self.cfg, self.wl, self.sess, self.dec
+        k, v = wl.append(t)
+        sess.append(k, v)
+        sess.torch.cuda.synchronize()
+        sess.ctx.fc_check_device_state()
+        filled = []
+        for b in range(cfg.batch):
+            page = dec.append(b)
+            if page is not None:
+                for h in range(cfg.num_kv_heads):
+                    self.o_table[b, h, page] = self.o_free[(b, h)].pop()      # the last block of the free list
+                self.appended_pages.append((b, page))
+            if wl.cur_len[b] % 16 == 0:
+                filled.append((b, wl.cur_len[b] // 16 - 1))
+            self.mm[b] = oracle.seq_build_minmax(wl.k[b], wl.cur_len[b])
+        assert sess.context_lens.cpu().tolist() == wl.cur_len == dec.ctx
+        np.testing.assert_array_equal(sess.block_table.cpu().numpy(), self.o_table)
+        fb, fc = sess.free_blocks.cpu().numpy(), sess.free_count.cpu().numpy()
+        for (b, h), fl in self.o_free.items():
+            assert fc[b, h] == len(fl) and list(fb[b, h, :len(fl)]) == fl
+        sel = sess.selected()
+        for (b, h), pages in sel.items():
+            np.testing.assert_array_equal(pages, dec.sel[(b, h)])
+        self.check_minmax()
+        # the page being appended to: valid tokens bit for bit, in every head's HBM block
+        i16 = sess.torch.int16
+        for b in range(cfg.batch):
+            p = (wl.cur_len[b] - 1) // 16
+            ntok = wl.cur_len[b] - 16 * p
+            blocks = sess.torch.tensor(self.o_table[b, :, p].astype(np.int64), device=sess.kv_pool.device)
+            got = sess.kv_pool[blocks].cpu().view(i16).numpy().view(np.uint16)
+            for h in range(cfg.num_kv_heads):
+                kp, vp = wl.k[b][h, 16 * p:16 * p + 16], wl.v[b][h, 16 * p:16 * p + 16]
+                np.testing.assert_array_equal(got[h][:ntok * 128], kp.reshape(-1)[:ntok * 128])
+                np.testing.assert_array_equal(got[h][2048:].reshape(128, 16)[:, :ntok], vp.T[:, :ntok])
+        # pages that just filled: the stable heads' host copy holds exactly that page
+        host = sess.host_pool.view(i16).numpy().view(np.uint16)
+        for b, p in filled:
+            for h in range(cfg.num_kv_heads):
+                if cfg.stable[h]:
+                    hb = sess._hbt[b, h, p]
+                    exp = native_page(wl.k[b][h, 16 * p:16 * p + 16], wl.v[b][h, 16 * p:16 * p + 16])
+                    np.testing.assert_array_equal(host[hb], exp)
 
     def step(self, t: int, check_pool: bool = True):
         cfg, wl, sess, dec = self.cfg, self.wl, self.sess, self.dec
+        # appends start after step 0: the harness begins with nothing of a stable head resident (the first
+        # rerank is a cold fill), whereas after a real prefill the partial last page would already be in HBM
+        if cfg.append_tokens and 1 <= t <= cfg.append_tokens:
+            self.append_token(t)
         if t > 0:
             changed = wl.advance(t, sess.selected() if cfg.dynamics == "plant_nonresident" else None)
             if changed:
                 sess.refresh(changed)
                 for b in sorted({c[0] for c in changed}):
-                    self.mm[b] = oracle.seq_build_minmax(wl.k[b], cfg.ctx[b])
+                    self.mm[b] = oracle.seq_build_minmax(wl.k[b], wl.cur_len[b])
         q = wl.queries(t)
         sess.set_queries(q)
         sess.step(t)
@@ -100,8 +155,8 @@ class ParityRun:
             promoted_gpu = sess.promoted_count.cpu().numpy()
             step_promoted = 0
             for b in range(cfg.batch):
-                n = cfg.num_pages(b)
-                forced = n - 1 if cfg.ctx[b] % 16 else -1
+                n = self.pages_now(b)
+                forced = n - 1 if wl.cur_len[b] % 16 else -1
                 old = {h: dec.sel[(b, h)].copy() for h in range(cfg.num_kv_heads) if cfg.stable[h]}
                 dec.rerank(b, q[b], self.mm[b])
                 for h in range(cfg.num_kv_heads):
@@ -126,7 +181,7 @@ class ParityRun:
             fb = sess.free_blocks.cpu().numpy()
             fc = sess.free_count.cpu().numpy()
             for (b, h), fl in self.o_free.items():
-                assert fc[b, h] == len(fl) and list(fb[b, h, :len(fl)]) == fl
+                assert fc[b, h] == len(fl) and list(fb[b, h, :len(fl)]) == fl, (b, h, fl, fb[b, h, :fc[b, h]])
             if check_pool:
                 self.check_resident_pages(bt_gpu)
         # attention, evaluated by the oracle on the (audited) selection
@@ -146,8 +201,8 @@ class ParityRun:
         pages = sess.resident_pages.cpu().numpy()
         cnt = sess.resident_count.cpu().numpy()
         for b in range(cfg.batch):
-            n = cfg.num_pages(b)
-            forced = n - 1 if cfg.ctx[b] % 16 else -1
+            n = self.pages_now(b)
+            forced = n - 1 if self.wl.cur_len[b] % 16 else -1
             dec.rerank_unstable(b, q[b], self.mm[b])
             for h in range(cfg.num_kv_heads):
                 if cfg.stable[h]:
@@ -172,7 +227,7 @@ class ParityRun:
         got = pool[blocks].cpu().view(self.sess.torch.int16).numpy().view(np.uint16)
         for i, (b, h, p) in enumerate(todo):
             assert bt_gpu[b, h, p] > 0
-            ntok = min(16, cfg.ctx[b] - 16 * p)
+            ntok = min(16, wl.cur_len[b] - 16 * p)
             kp, vp = wl.k[b][h, 16 * p:16 * p + 16], wl.v[b][h, 16 * p:16 * p + 16]
             exp = native_page(kp, vp)
             if ntok == 16:

@@ -70,3 +70,4 @@ def test_struct_sizes_match_the_c_layout():
     assert C.sizeof(binding.fc_rerank_args) == 80
     assert C.sizeof(binding.fc_attn_args) == 96
     assert C.sizeof(binding.fc_promote_args) == 136
+    assert C.sizeof(binding.fc_append_args) == 136

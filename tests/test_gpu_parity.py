@@ -136,3 +136,57 @@ def test_paper_variant_full_size_sampled_rows():
         r.run()
     finally:
         r.close()
+
+
+# ---- contexts that grow during the run: KV append, incremental MinMax, offload of pages as they fill --
+@pytest.mark.parametrize("ctx,R", [(2048, 2), (2048 + 9, 2), (300, 3)])
+def test_append_tiny_growing_context(ctx, R):
+    import dataclasses
+    cfg = dataclasses.replace(synth.make_config(1, ctx=ctx, steps=41), append_tokens=40, rerank_interval=R,
+                              name=f"append_tiny_{ctx}_{R}")
+    _run(cfg)
+
+
+def test_append_reduced_config2_growing_context():
+    import dataclasses
+    cfg = dataclasses.replace(synth.make_config(2, batch=3, ctx=4096 + 7, steps=37), append_tokens=36,
+                              dynamics="static", name="append_cfg2")
+    r = _run(cfg)
+    assert len(r.appended_pages) == 3 * 2      # tokens 4103..4138 start pages 257 and 258 in each sequence
+
+
+def test_append_paper_variant_growing_context():
+    import dataclasses
+    cfg = dataclasses.replace(synth.make_config(2, batch=2, ctx=2048 + 15, steps=21), append_tokens=20,
+                              dynamics="static", name="append_paper_variant")
+    _run(cfg, unstable_topk=True)
+
+
+def test_bulk_offload_copies_exact_pages_and_skips_bad_pairs():
+    import torch
+    from paper_2511_00868_amd.session import DecodeSession
+    cfg = synth.make_config(1, ctx=1000, steps=1)
+    wl = synth.Workload(cfg)
+    s = DecodeSession(cfg, wl)
+    try:
+        # head 1 is unstable: all of its 63 pages sit in HBM; offload a shuffled subset to fresh host blocks
+        bt = s.block_table.cpu().numpy()[0, 1, :63]
+        rng = np.random.default_rng(1)
+        pages = rng.permutation(63)[:40]
+        host = torch.zeros((64, 4096), dtype=torch.bfloat16, pin_memory=True)
+        pairs = np.stack([bt[pages], np.arange(1, 41)], axis=1).astype(np.int32)
+        pairs = np.concatenate([pairs, np.array([[0, 50], [5, 0], [10 ** 6, 51], [3, 64]], dtype=np.int32)])  # skipped
+        pd = torch.from_numpy(pairs).cuda()
+        s.ctx.fc_offload_pages(s.kv_pool, s.num_pool_blocks, host, 64, pd, len(pairs))
+        torch.cuda.synchronize()
+        got = host.view(torch.int16).numpy().view(np.uint16)
+        from parity_util import native_page
+        for i, p in enumerate(pages):
+            exp = native_page(wl.k[0][1, 16 * p:16 * p + 16], wl.v[0][1, 16 * p:16 * p + 16])
+            if p == 62:      # the partial page: pad tokens are copied as they are, compare the valid ones
+                np.testing.assert_array_equal(got[i + 1][:8 * 128], exp[:8 * 128])
+            else:
+                np.testing.assert_array_equal(got[i + 1], exp)
+        assert not got[41:].any() and not got[0].any()
+    finally:
+        s.close()

@@ -330,3 +330,25 @@ def test_paper_variant_of_unstable_heads_selects_per_step_and_reduces_to_dense_w
         dec8.rerank_unstable(0, qt, mm)
         s = oracle.page_scores(qt[cfg.group:2 * cfg.group], mm[1])
         np.testing.assert_array_equal(dec8.sel[(0, 1)], oracle.select_topk(s, cfg.ctx[0], 8))
+
+
+def test_appended_tokens_join_the_sequence_and_the_started_page_joins_the_selection():
+    rng = np.random.default_rng(31)
+    D, P, ctx0, extra = 128, 16, 30, 5           # tokens 30, 31 complete page 1; token 32 starts page 2
+    k, v = rand_bf16(rng, (48, D)), rand_bf16(rng, (48, D))
+    q = rand_bf16(rng, (4, D))
+    dec = oracle.OracleDecoder(1, 4, 1, [ctx0], [True], [1], 100)
+    mm = oracle.seq_build_minmax(k[None], ctx0)
+    dec.rerank(0, q, mm)
+    assert list(dec.sel[(0, 0)]) == [1]                    # the partial page is the whole budget
+    started = [dec.append(0) for _ in range(extra)]
+    assert started == [None, None, 2, None, None] and dec.ctx[0] == 35
+    assert list(dec.sel[(0, 0)]) == [1, 2]
+    out, _ = dec.attend(0, q, k[None], v[None])
+    toks = np.arange(16, 35)
+    for g in range(4):
+        ref, _ = dense_attention_numpy(q[g], k[toks], v[toks], len(toks), 1 / np.sqrt(D))
+        np.testing.assert_allclose(out[g], ref, rtol=1e-12, atol=1e-13)
+    mm2 = oracle.seq_build_minmax(k[None], 35)
+    dec.rerank(0, q, mm2)                                   # next rerank: budget 1 -> only the partial page stays
+    assert list(dec.sel[(0, 0)]) == [2]
