@@ -52,6 +52,11 @@ def lib():
         L.fco_seq_attention.argtypes = [u16p, u16p, u16p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                         C.c_int, i32p, C.c_int, i32p, C.c_double, f64p, f64p]
         L.fco_threads.restype = C.c_int
+        L.fco_rco.argtypes = [i32p, i32p, C.c_int, C.c_int]
+        L.fco_rco.restype = C.c_double
+        L.fco_stability.argtypes = [i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, f64p]
+        L.fco_bottom_counts.argtypes = [f64p, C.c_int, C.c_int, i32p]
+        L.fco_classify.argtypes = [i32p, C.c_int, C.c_int, C.c_int, u8p]
         _lib = L
     return _lib
 
@@ -131,6 +136,40 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, ctx: int, pages, scal
                         _p(pages, C.c_int32), len(pages), scale, _p(out, C.c_double), C.byref(lse),
                         C.byref(ws))
     return out, lse.value, ws.value
+
+
+# ---- offline head-stability profiling (Sec. 2.2, 2.3) -------------------------------------------
+def rco(a, b, n_t: int) -> float:
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    b = np.ascontiguousarray(b, dtype=np.int32)
+    assert len(a) == len(b)
+    return float(lib().fco_rco(_p(a, C.c_int32), _p(b, C.c_int32), len(a), n_t))
+
+
+def stability(traces: np.ndarray, num_pages, W: int) -> np.ndarray:
+    """traces: int32 [steps, heads, K]; num_pages: [steps] -> float64 [steps - W + 1, heads]."""
+    traces = np.ascontiguousarray(traces, dtype=np.int32)
+    steps, heads, K = traces.shape
+    npg = np.ascontiguousarray(num_pages, dtype=np.int32)
+    ts = np.zeros((max(steps - W + 1, 0), heads), dtype=np.float64)
+    if len(ts):
+        lib().fco_stability(_p(traces, C.c_int32), _p(npg, C.c_int32), steps, heads, K, W, _p(ts, C.c_double))
+    return ts
+
+
+def bottom_counts(ts: np.ndarray, counts: Optional[np.ndarray] = None) -> np.ndarray:
+    ts = np.ascontiguousarray(ts, dtype=np.float64)
+    windows, heads = ts.shape
+    out = np.zeros(heads, dtype=np.int32) if counts is None else np.ascontiguousarray(counts, dtype=np.int32).copy()
+    lib().fco_bottom_counts(_p(ts, C.c_double), windows, heads, _p(out, C.c_int32))
+    return out
+
+
+def classify(counts, num: int = 1, den: int = 4) -> np.ndarray:
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    flags = np.zeros(len(counts), dtype=np.uint8)
+    lib().fco_classify(_p(counts, C.c_int32), len(counts), num, den, _p(flags, C.c_uint8))
+    return flags
 
 
 # ---- whole-sequence routines --------------------------------------------------------------------

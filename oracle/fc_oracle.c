@@ -24,12 +24,16 @@
  *                         block) copy list is produced.
  *   fco_attention         Sec. 3.1: softmax attention of one query over the tokens of a given page set
  *                         (all pages = ordinary dense attention).
+ *   fco_rco, fco_stability, fco_bottom_counts, fco_classify
+ *                         Sec. 2.2 / 2.3: random-corrected overlap, temporal stability score, and the
+ *                         stable / unstable classification of heads (documented at their definitions).
  *
  * Pins (tests/test_oracle_pins.py): dense numpy softmax attention when the page set is everything;
  * weights sum to one; any partition of the page set merges to the same (out, lse); s_p bounds q.k of
  * every key of the page and equals it for single-key / identical-key pages; closed forms for q >= 0
  * and q <= 0; positive homogeneity; numpy lexsort for the selection; set-algebra invariants and the
- * paper's four-page placement example for the recycling; the paper's 192 MB / 70 % byte arithmetic.
+ * paper's four-page placement example for the recycling; the paper's 192 MB / 70 % byte arithmetic;
+ * RCO anchors 0 (chance) and 1 (identical sets), numpy set arithmetic and argsort for the profiling.
  * Unpinned: whether this score keeps model accuracy (needs the paper's models and datasets).
  */
 #include <math.h>
@@ -261,4 +265,67 @@ int fco_threads(void)
     }
 #endif
     return n;
+}
+
+/* ---- offline head-stability profiling (Sec. 2.2, 2.3) ----------------------------------------------
+ * traces: [steps][heads][K] page ids of the top-K selection of every (layer, head) at every decode step
+ * of one sample, each list ascending; num_pages[steps]: candidate pages N_t at each step.
+ *
+ * fco_rco            random-corrected overlap of two selections (Sec. 2.2, first equation):
+ *                    max(0, (|S_s n S_t| / K - K / N_t) / (1 - K / N_t)); defined 0 when K == N_t.
+ * fco_stability      temporal stability score (Sec. 2.2, second equation): mean of RCO(s, t) over
+ *                    t = s+1 .. s+W-1, for every window start s with s+W-1 < steps.  ts: [steps-W+1][heads].
+ * fco_bottom_counts  Sec. 2.3: for every window, the heads whose score lies in the lowest quarter
+ *                    (floor(heads / 4) heads; ties to the lower head index) get one count each.
+ * fco_classify       Sec. 2.3: the floor(heads * num / den) heads counted most often are unstable
+ *                    (ties to the lower head index); flags[h] = 1 for unstable.
+ */
+double fco_rco(const int32_t *a, const int32_t *b, int K, int n_t)
+{
+    int inter = 0;
+    for (int i = 0; i < K; ++i)
+        for (int j = 0; j < K; ++j)
+            if (a[i] >= 0 && a[i] == b[j]) { ++inter; break; }
+    if (n_t <= K) return 0.0;
+    double chance = (double)K / (double)n_t;
+    double r = ((double)inter / (double)K - chance) / (1.0 - chance);
+    return r > 0.0 ? r : 0.0;
+}
+
+void fco_stability(const int32_t *traces, const int32_t *num_pages, int steps, int heads, int K, int W,
+                   double *ts)
+{
+    for (int s = 0; s + W - 1 < steps; ++s)
+        for (int h = 0; h < heads; ++h) {
+            double acc = 0.0;
+            for (int t = s + 1; t <= s + W - 1; ++t)
+                acc += fco_rco(traces + ((size_t)s * heads + h) * K, traces + ((size_t)t * heads + h) * K, K,
+                               num_pages[t]);
+            ts[(size_t)s * heads + h] = acc / (double)(W - 1);
+        }
+}
+
+void fco_bottom_counts(const double *ts, int windows, int heads, int32_t *counts)
+{
+    int q = heads / 4;
+    for (int w = 0; w < windows; ++w)
+        for (int h = 0; h < heads; ++h) {
+            int rank = 0;   /* heads that come before h in (score asc, index asc) order */
+            for (int g = 0; g < heads; ++g) {
+                double x = ts[(size_t)w * heads + g], y = ts[(size_t)w * heads + h];
+                if (x < y || (x == y && g < h)) ++rank;
+            }
+            if (rank < q) counts[h] += 1;
+        }
+}
+
+void fco_classify(const int32_t *counts, int heads, int num, int den, uint8_t *flags)
+{
+    int want = (int)(((long long)heads * num) / den);
+    for (int h = 0; h < heads; ++h) {
+        int rank = 0;       /* heads counted more often, or as often with a lower index */
+        for (int g = 0; g < heads; ++g)
+            if (counts[g] > counts[h] || (counts[g] == counts[h] && g < h)) ++rank;
+        flags[h] = rank < want ? 1 : 0;
+    }
 }

@@ -352,3 +352,63 @@ def test_appended_tokens_join_the_sequence_and_the_started_page_joins_the_select
     mm2 = oracle.seq_build_minmax(k[None], 35)
     dec.rerank(0, q, mm2)                                   # next rerank: budget 1 -> only the partial page stays
     assert list(dec.sel[(0, 0)]) == [2]
+
+
+# ---- offline stability profiling (Sec. 2.2, 2.3) -------------------------------------------------
+def test_rco_anchors_and_closed_form():
+    assert oracle.rco([1, 5, 9, 12], [1, 5, 9, 12], 100) == 1.0               # identical sets
+    assert oracle.rco([0, 1], [1, 2], 4) == 0.0                               # overlap 1/2 = K/N: chance level
+    assert oracle.rco([0, 1], [2, 3], 4) == 0.0                               # below chance clamps to 0
+    assert oracle.rco([0, 1, 2, 3], [0, 1, 2, 3], 4) == 0.0                   # K = N: defined 0
+    # (I/K - K/N) / (1 - K/N) with I = 3, K = 4, N = 64
+    assert abs(oracle.rco([3, 7, 20, 41], [3, 7, 41, 50], 64) - (0.75 - 0.0625) / 0.9375) < 1e-15
+    assert oracle.rco([3, 7, 20, 41], [41, 3, 50, 7], 64) == oracle.rco([3, 7, 20, 41], [3, 7, 41, 50], 64)
+
+
+def test_uncorrected_overlap_of_random_draws_is_at_chance_level():
+    """Sec. 2.2: the correction subtracts the hypergeometric mean K/N; with the clamp at 0 the mean RCO of
+    independent random selections stays small, while identical selections give 1."""
+    rng = np.random.default_rng(0)
+    K, N = 16, 256
+    vals = [oracle.rco(np.sort(rng.choice(N, K, replace=False)), np.sort(rng.choice(N, K, replace=False)), N)
+            for _ in range(400)]
+    assert 0.0 <= np.mean(vals) < 0.03 and max(vals) < 0.3
+
+
+def test_stability_score_counts_and_classification_against_numpy():
+    rng = np.random.default_rng(4)
+    steps, heads, K, W = 24, 8, 6, 5
+    N = np.arange(40, 40 + steps)
+    traces = np.stack([np.stack([np.sort(rng.choice(N[t], K, replace=False)) for _ in range(heads)])
+                       for t in range(steps)]).astype(np.int32)
+    traces[:, 2] = traces[0, 2]                        # head 2 never changes: perfectly stable
+    traces[1:, 5, :4] = traces[0, 5, :4]               # head 5 keeps 4 of 6 pages (when sorted order allows)
+    traces[:, 5].sort(axis=1)
+    ts = oracle.stability(traces, N, W)
+    assert ts.shape == (steps - W + 1, heads)
+    ref = np.zeros_like(ts)
+    for s in range(steps - W + 1):
+        for h in range(heads):
+            r = []
+            for t in range(s + 1, s + W):
+                inter = len(set(traces[s, h]) & set(traces[t, h]))
+                c = K / N[t]
+                r.append(max(0.0, (inter / K - c) / (1 - c)))
+            ref[s, h] = np.mean(r)
+    np.testing.assert_allclose(ts, ref, rtol=1e-14, atol=1e-16)
+    assert np.all(ts[:, 2] == 1.0)
+    counts = oracle.bottom_counts(ts)
+    ref_counts = np.zeros(heads, dtype=np.int32)
+    for w in range(len(ts)):
+        order = np.lexsort((np.arange(heads), ts[w]))  # score ascending, index ascending
+        ref_counts[order[:heads // 4]] += 1
+    np.testing.assert_array_equal(counts, ref_counts)
+    assert counts.sum() == len(ts) * (heads // 4) and counts[2] == 0
+    flags = oracle.classify(counts)
+    order = np.lexsort((np.arange(heads), -counts))
+    ref_flags = np.zeros(heads, dtype=np.uint8)
+    ref_flags[order[:heads // 4]] = 1
+    np.testing.assert_array_equal(flags, ref_flags)
+    assert flags.sum() == 2 and flags[2] == 0
+    # counts accumulate over samples
+    np.testing.assert_array_equal(oracle.bottom_counts(ts, counts), 2 * counts)
