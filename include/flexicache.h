@@ -246,6 +246,32 @@ int fc_append_kv(fc_ctx *ctx, const fc_append_args *args, void *stream);
 int fc_offload_pages(fc_ctx *ctx, const void *kv_pool, int64_t num_pool_blocks, void *host_pool,
                      int64_t num_host_blocks, const int32_t *pairs, int32_t n_pairs, void *stream);
 
+/* ---- offline head-stability profiling (Sec. 2.2, 2.3) ------------------------------------------- */
+
+/* One sample's top-K traces -> temporal stability scores and bottom-quartile counts.
+ *   traces      dev int32 [steps][heads][topk]: the page list every (layer, head) selected at every
+ *               decode step, ascending, -1 padded (what fc_rerank_topk writes); `heads` counts all
+ *               (layer, head) pairs that are profiled together
+ *   num_pages   dev int32 [steps]: candidate pages N_t at each step
+ *   ts_out      dev fp64 [steps - window + 1][heads]:
+ *               TS(s) = mean over t = s+1 .. s+window-1 of RCO(s, t),
+ *               RCO(s, t) = max(0, (|S_s n S_t| / topk - topk / N_t) / (1 - topk / N_t)), 0 if N_t <= topk
+ *   bottom_counts  dev int32 [heads], in/out: for every window the floor(heads / 4) heads with the lowest
+ *               TS (ties to the lower head index) are incremented; call once per sample to accumulate. */
+typedef struct {
+    const int32_t *traces;
+    const int32_t *num_pages;
+    int32_t steps, heads, topk, window;
+    double *ts_out;
+    int32_t *bottom_counts;
+} fc_stability_args;
+int fc_stability_profile(fc_ctx *ctx, const fc_stability_args *args, void *stream);
+
+/* Sec. 2.3: the floor(heads * num / den) heads counted most often in the bottom quartile (ties to the
+ * lower head index) are unstable: unstable_out[h] = 1 (dev uint8 [heads]); the paper uses 1/4. */
+int fc_classify_heads(fc_ctx *ctx, const int32_t *bottom_counts, int32_t heads, int32_t num, int32_t den,
+                      uint8_t *unstable_out, void *stream);
+
 /* Reads (and clears) the device-side error word set by the bookkeeping kernels (a head owning too
  * few blocks, an id out of range that was clamped).  Synchronises `stream`.  Returns FC_OK or
  * FC_ERR_STATE. */

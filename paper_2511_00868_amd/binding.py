@@ -23,9 +23,15 @@ class fc_append_args(C.Structure):
                 ("stable_flag", C.c_void_p), ("batch", C.c_int32)]
 
 
+class fc_stability_args(C.Structure):
+    _fields_ = [("traces", C.c_void_p), ("num_pages", C.c_void_p), ("steps", C.c_int32), ("heads", C.c_int32),
+                ("topk", C.c_int32), ("window", C.c_int32), ("ts_out", C.c_void_p), ("bottom_counts", C.c_void_p)]
+
+
 EXPORTS = ["fc_workspace_bytes", "fc_host_scratch_bytes", "fc_create", "fc_destroy", "fc_status_string",
            "fc_last_error", "fc_write_kv_pages", "fc_build_minmax", "fc_rerank_topk", "fc_promote_pages",
-           "fc_sparse_decode_attn", "fc_append_kv", "fc_offload_pages", "fc_check_device_state", "fc_profile_begin", "fc_profile_end"]
+           "fc_sparse_decode_attn", "fc_append_kv", "fc_offload_pages", "fc_stability_profile", "fc_classify_heads",
+           "fc_check_device_state", "fc_profile_begin", "fc_profile_end"]
 
 
 class fc_config(C.Structure):
@@ -90,6 +96,8 @@ def load() -> C.CDLL:
         L.fc_append_kv.argtypes = [C.c_void_p, C.POINTER(fc_append_args), C.c_void_p]
         L.fc_offload_pages.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                        C.c_void_p]
+        L.fc_stability_profile.argtypes = [C.c_void_p, C.POINTER(fc_stability_args), C.c_void_p]
+        L.fc_classify_heads.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.fc_check_device_state.argtypes = [C.c_void_p, C.c_void_p]
         L.fc_profile_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.fc_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
@@ -212,6 +220,16 @@ class Context:
                          stream=None):
         self._check(self.lib.fc_offload_pages(self.handle, _ptr(kv_pool), num_pool_blocks, _ptr(host_pool),
                                               num_host_blocks, _ptr(pairs), n_pairs, self._stream(stream)))
+
+    def fc_stability_profile(self, *, traces, num_pages, steps: int, heads: int, topk: int, window: int, ts_out,
+                             bottom_counts, stream=None):
+        a = fc_stability_args(_ptr(traces), _ptr(num_pages), steps, heads, topk, window, _ptr(ts_out),
+                              _ptr(bottom_counts))
+        self._check(self.lib.fc_stability_profile(self.handle, C.byref(a), self._stream(stream)))
+
+    def fc_classify_heads(self, bottom_counts, heads: int, unstable_out, num: int = 1, den: int = 4, stream=None):
+        self._check(self.lib.fc_classify_heads(self.handle, _ptr(bottom_counts), heads, num, den, _ptr(unstable_out),
+                                               self._stream(stream)))
 
     def fc_check_device_state(self, stream=None):
         self._check(self.lib.fc_check_device_state(self.handle, self._stream(stream)))

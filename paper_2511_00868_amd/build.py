@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflexicache.so")
-SOURCES = ["fc_context.hip", "fc_pages.hip", "fc_attn.hip", "fc_rerank.hip", "fc_promote.hip", "fc_append.hip"]
+SOURCES = ["fc_context.hip", "fc_pages.hip", "fc_attn.hip", "fc_rerank.hip", "fc_promote.hip", "fc_append.hip", "fc_stability.hip"]
 # packed fp32 VALU forms are switched off on purpose (they have produced silent wrong results on the
 # target machines); hipcc's host pass does not know the feature and says so, which is harmless.
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
