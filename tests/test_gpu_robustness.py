@@ -1,0 +1,162 @@
+"""GPU tests of error paths, copy/compute ordering and per-sequence rerank phases.  Every kernel exits
+normally in all of them: errors are forced from the host (bad arguments, too few blocks)."""
+import ctypes as C
+import dataclasses
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_00868_amd import binding, synth
+from paper_2511_00868_amd.session import DecodeSession
+
+pytestmark = pytest.mark.gpu
+
+
+def test_bad_arguments_are_rejected_before_anything_is_launched():
+    import torch
+    ctx = binding.Context(num_q_heads=8, num_kv_heads=2, max_batch=2, max_pages_per_seq=16, max_topk=4)
+    try:
+        q = torch.zeros((2, 8, 128), dtype=torch.bfloat16, device="cuda")
+        out = torch.zeros((2, 8, 128), dtype=torch.float32, device="cuda")
+        tbl = torch.zeros((2, 2, 16), dtype=torch.int32, device="cuda")
+        lens = torch.ones(2, dtype=torch.int32, device="cuda")
+        pool = torch.zeros((4, 4096), dtype=torch.bfloat16, device="cuda")
+        ok = dict(q=q, kv_pool=pool, num_pool_blocks=4, block_table=tbl, context_lens=lens, stable_flag=[False, False],
+                  topk_pages=None, topk_count=None, batch=2, out=out)
+        for bad in (dict(q=None), dict(out=None), dict(batch=0), dict(batch=3), dict(num_pool_blocks=1),
+                    dict(head_subset=7), dict(stable_flag=[True, False])):       # stable head without lists
+            with pytest.raises(binding.FlexiCacheError) as e:
+                ctx.fc_sparse_decode_attn(**{**ok, **bad})
+            assert e.value.status == binding.FC_ERR_INVALID_ARG and "fc_sparse_decode_attn" in str(e.value)
+        with pytest.raises(binding.FlexiCacheError) as e:
+            ctx.fc_rerank_topk(q=q, minmax=None, context_lens=lens, stable_flag=[True, False], k_per_seq=lens, batch=2,
+                               topk_pages=tbl, topk_count=lens)
+        assert e.value.status == binding.FC_ERR_INVALID_ARG
+        s = torch.cuda.current_stream()
+        with pytest.raises(binding.FlexiCacheError) as e:   # main and side stream must differ
+            ctx.fc_promote_pages(new_pages=tbl, new_count=lens, resident_pages=tbl, resident_count=lens, block_table=tbl,
+                                 host_block_table=tbl, free_blocks=tbl, free_count=lens, stable_flag=[True, False],
+                                 kv_pool=pool, num_pool_blocks=4, host_pool=pool, num_host_blocks=4, batch=2,
+                                 main_stream=s, side_stream=s)
+        assert e.value.status == binding.FC_ERR_INVALID_ARG
+        with pytest.raises(binding.FlexiCacheError):
+            ctx.fc_write_kv_pages(q, q, 17, tbl, pool, 4)                          # more pages than max_pages_per_seq
+        with pytest.raises(binding.FlexiCacheError):
+            ctx.fc_build_minmax(pool, 4, tbl, None, 3, 100, q)                     # n_list must equal the page count
+        ctx.fc_sparse_decode_attn(**ok)                                            # the good call still works
+        torch.cuda.synchronize()
+        ctx.fc_check_device_state()
+    finally:
+        ctx.close()
+    with pytest.raises(binding.FlexiCacheError):
+        binding.Context(num_q_heads=8, num_kv_heads=2, max_batch=2, max_pages_per_seq=16, max_topk=4, head_dim=64)
+
+
+def test_too_few_blocks_is_reported_not_faulted():
+    cfg = synth.make_config(1, steps=1)
+    wl = synth.Workload(cfg)
+    s = DecodeSession(cfg, wl)
+    try:
+        s.free_count[0, 0] = 3                    # the stable head will select 8 pages but owns 3 blocks
+        s.set_queries(wl.queries(0))
+        s.rerank()
+        s.promote()
+        s.torch.cuda.synchronize()
+        with pytest.raises(binding.FlexiCacheError) as e:
+            s.ctx.fc_check_device_state()
+        assert e.value.status == binding.FC_ERR_STATE
+        s.ctx.fc_check_device_state()             # the error word was cleared by the read
+        assert int(s.promoted_count[0, 0]) == 8 and int((s.block_table[0, 0] > 0).sum()) == 3
+    finally:
+        s.close()
+
+
+def _run_steps_against_oracle(s, wl, cfg, steps, before_step=None):
+    dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, cfg.topk,
+                               cfg.rerank_interval)
+    mm = [oracle.seq_build_minmax(wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]
+    for t in range(steps):
+        q = wl.queries(t)
+        s.set_queries(q)
+        if before_step:
+            before_step(t)
+        s.step(t)
+        s.torch.cuda.synchronize()
+        s.ctx.fc_check_device_state()
+        got = s.out.cpu().numpy().astype(np.float64)
+        assert np.all(np.isfinite(got)), "a poisoned block was read before its copy had landed"
+        sel = s.selected()
+        for b in range(cfg.batch):
+            if cfg.is_rerank_step(t):
+                dec.rerank(b, q[b], mm[b])
+            ref, _ = dec.attend(b, q[b], wl.k[b], wl.v[b], override=sel)
+            err = np.abs(got[b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+            assert err.max() <= 2e-3
+
+
+@pytest.mark.parametrize("mode", [binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_MEMCPY])
+def test_attention_waits_for_delayed_copies_into_poisoned_blocks(mode):
+    """Every block a promoted page will land in holds NaN until its copy arrives, and the copy stream is
+    held back by a long sleep kernel before each rerank step: the stable heads' attention must still see
+    the copied pages (a premature read would surface as NaN)."""
+    import torch
+    cfg = synth.make_config(5, batch=2, ctx=4096, steps=9)
+    wl = synth.Workload(cfg)
+    s = DecodeSession(cfg, wl, promote_mode=mode)
+    try:
+        fb, fc = s.free_blocks.cpu().numpy(), s.free_count.cpu().numpy()
+        ids = [int(x) for b in range(cfg.batch) for h in range(cfg.num_kv_heads) for x in fb[b, h, :fc[b, h]]]
+        s.kv_pool[torch.tensor(ids, device="cuda")] = float("nan")
+
+        def hold_back_copies(t):
+            if cfg.is_rerank_step(t):
+                with torch.cuda.stream(s.copy):
+                    torch.cuda._sleep(20_000_000)        # ~10 ms at the GPU's clock
+                # recycled blocks are about to be overwritten by copies: poison them as the evicted pages leave
+        _run_steps_against_oracle(s, wl, cfg, 9, hold_back_copies)
+    finally:
+        s.close()
+
+
+def test_per_sequence_rerank_phases():
+    """rerank_mask staggers the sequences (the paper pauses one request at a time, Sec. 3.3): sequence b
+    reranks when (t + b) mod R == 0; the others keep their lists, tables and blocks untouched."""
+    import torch
+    cfg = synth.make_config(2, batch=4, ctx=2048 + 5, steps=8)
+    wl = synth.Workload(dataclasses.replace(cfg, dynamics="static"))
+    s = DecodeSession(cfg, wl)
+    try:
+        R = cfg.rerank_interval
+        dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, cfg.topk, R)
+        mm = [oracle.seq_build_minmax(wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]
+        warmed = set()
+        for t in range(2 * R):
+            q = wl.queries(t)
+            s.set_queries(q)
+            # every sequence needs one cold fill first; afterwards they take turns
+            mask = [1 if (b not in warmed or (t + b) % R == 0) else 0 for b in range(cfg.batch)]
+            md = torch.tensor(mask, dtype=torch.uint8, device="cuda")
+            before = (s.resident_pages.clone(), s.block_table.clone(), s.free_blocks.clone())
+            s.rerank(rerank_mask=md)
+            s.promote(rerank_mask=md)
+            s.attend()
+            torch.cuda.synchronize()
+            s.ctx.fc_check_device_state()
+            sel = s.selected()
+            got = s.out.cpu().numpy().astype(np.float64)
+            for b in range(cfg.batch):
+                if mask[b]:
+                    dec.rerank(b, q[b], mm[b])
+                    warmed.add(b)
+                    for h in range(cfg.num_kv_heads):
+                        if cfg.stable[h]:
+                            assert set(sel[(b, h)]) == set(dec.sel[(b, h)])
+                else:
+                    for old, new in zip(before, (s.resident_pages, s.block_table, s.free_blocks)):
+                        assert torch.equal(old[b], new[b])
+                    assert int(s.promoted_count[b].sum()) == 0
+                ref, _ = dec.attend(b, q[b], wl.k[b], wl.v[b])
+                assert (np.abs(got[b] - ref).max(axis=1) / np.abs(ref).max(axis=1)).max() <= 2e-3
+    finally:
+        s.close()
