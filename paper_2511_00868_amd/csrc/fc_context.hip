@@ -155,10 +155,15 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
     c->copies_pending = false;
     c->unstable_pending = false;
     c->promote_calls = 0;
-    c->gather_blocks = 32;   // measured: 16 starves PCIe, 64+ slows a concurrent attention kernel more
+    c->gather_blocks = 32;
     if (const char *env = getenv("FC_GATHER_BLOCKS")) {
         const int v = atoi(env);
         if (v >= 1 && v <= 4096) c->gather_blocks = v;
+    }
+    c->gather_threads = 64;
+    if (const char *env = getenv("FC_GATHER_THREADS")) {
+        const int v = atoi(env);
+        if (v == 64 || v == 128 || v == 256) c->gather_threads = v;
     }
     c->err[0] = 0;
     *out = c;

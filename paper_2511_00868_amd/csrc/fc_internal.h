@@ -51,8 +51,8 @@ struct fc_ctx {
     bool copies_pending;
     bool unstable_pending;   // an FC_HEADS_UNSTABLE call has left partials that the next FC_HEADS_STABLE call merges
     unsigned promote_calls;
-    int gather_blocks;    // workgroups of the host->HBM gather kernel: few, the copies are PCIe bound and
-                          // must not crowd the attention kernel off the compute units
+    int gather_threads;   // threads per gather workgroup (64, 128 or 256)
+    int gather_blocks;    // workgroups of the host->HBM gather kernel (few and small: see fc_promote.hip)
     // kernel timing
     bool profiling;
     int prof_used;

@@ -9,9 +9,13 @@
 //   promoted pages, in ascending page order, take blocks from the front of that list; table entries
 //   of evicted pages become the null block 0; one (host block, HBM block) pair per promoted page is
 //   appended to a global copy list; the rest of the list becomes the new free list.
-// gather kernel, on the side stream after the recycle kernel: a capped number of workgroups walk the
-//   copy list and pull each 8 KiB page straight out of pinned host memory -- no host-side gather, no
-//   per-page API call, no host wait.  (FC_PROMOTE_MEMCPY instead hands the list to the host, which
+// gather kernel, on the side stream after the recycle kernel: a capped number of small workgroups walk
+//   the copy list and pull each 8 KiB page straight out of pinned host memory -- no host-side gather,
+//   no per-page API call, no host wait.  Its shape is chosen for the kernel that runs beside it: host
+//   reads take microseconds and hold up the memory pipeline of the compute unit they are issued from,
+//   and the attention kernel gives every compute unit an equal share, so it ends with the slowest one.
+//   32 single-wavefront workgroups with four 16 B loads in flight per lane keep PCIe saturated (~55 GB/s)
+//   while touching few compute units (measured rerank step: 286 us; 32 x 256 threads: 318; 256 x 64: 336).  (FC_PROMOTE_MEMCPY instead hands the list to the host, which
 //   issues one hipMemcpyAsync per page.)
 #include "fc_internal.h"
 
@@ -214,9 +218,13 @@ __global__ __launch_bounds__(256) void fc_gather_pages_kernel(const int32_t *__r
         if (dst <= 0) continue;
         const uint4 *s = host_pool + src * V;
         uint4 *d = kv_pool + dst * V;
-        const uint4 x0 = s[threadIdx.x], x1 = s[threadIdx.x + 256];
-        d[threadIdx.x] = x0;
-        d[threadIdx.x + 256] = x1;
+        for (int k = threadIdx.x; k < V; k += 4 * blockDim.x) {   // four 16 B loads in flight per thread
+            const uint4 x0 = s[k], x1 = s[k + blockDim.x], x2 = s[k + 2 * blockDim.x], x3 = s[k + 3 * blockDim.x];
+            d[k] = x0;
+            d[k + blockDim.x] = x1;
+            d[k + 2 * blockDim.x] = x2;
+            d[k + 3 * blockDim.x] = x3;
+        }
     }
 }
 
@@ -280,7 +288,7 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
 
     if (a->mode == FC_PROMOTE_GATHER) {
         FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
-        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(256), 0, ss, p.copy_list, p.counters + 2 + p.parity,
+        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, ss, p.copy_list, p.counters + 2 + p.parity,
                            p.list_capacity, (const uint4 *)a->host_pool, (uint4 *)a->kv_pool);
         FC_HIP(ctx, hipGetLastError());
     } else {
