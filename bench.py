@@ -102,6 +102,8 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket the attention kernel with HIP events")
     ap.add_argument("--paper-unstable-topk", action="store_true",
                     help="the paper's own treatment of unstable heads: rescored every step, top-K attention")
+    ap.add_argument("--append", action="store_true",
+                    help="grow every context by one token per step (fc_append_kv: page write, MinMax update, offload on fill)")
     ap.add_argument("--no-overlap", action="store_true", help="run rerank, promotion and attention back to back on one stream")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
@@ -116,11 +118,20 @@ def main():
 
     total_steps = args.warmup + args.steps
     cfg = synth.make_config(args.config, batch=args.batch, ctx=args.ctx, steps=total_steps)
+    diag_steps = min(args.steps, 32)
+    if args.append:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, append_tokens=total_steps + diag_steps, dynamics="static")
     t_gen = time.perf_counter()
     wl = synth.Workload(cfg)
     mode = binding.FC_PROMOTE_GATHER if args.promote_mode == "gather" else binding.FC_PROMOTE_MEMCPY
     sess = DecodeSession(cfg, wl, promote_mode=mode, attn_waves=args.attn_waves, unstable_topk=args.paper_unstable_topk)
     q_all = torch.stack([sess._bits_to_dev(wl.queries(t)) for t in range(total_steps)])
+    new_kv = None
+    if args.append:
+        toks = [wl.append(t) for t in range(total_steps + diag_steps)]
+        new_kv = (torch.stack([sess._bits_to_dev(k) for k, _ in toks]), torch.stack([sess._bits_to_dev(v) for _, v in toks]))
+    n_appended = [0]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
@@ -133,6 +144,10 @@ def main():
             e = torch.cuda.Event(enable_timing=True)
             e.record(main)
             marks.append(e)
+        if new_kv is not None and (t > 0 or n_appended[0] > 0):   # the first step is the cold fill
+            i = n_appended[0]
+            sess.append_dev(new_kv[0][i], new_kv[1][i])
+            n_appended[0] = i + 1
         sess.step(t)
 
     for t in range(args.warmup):
@@ -156,7 +171,7 @@ def main():
     is_rer_timed = [cfg.is_rerank_step(t) and any(cfg.stable) for t in range(args.warmup, total_steps)]
 
     # ---- diagnostic pass (untimed for `value`): per-step durations from one event per step ----------
-    diag = min(args.steps, 32)
+    diag = diag_steps
     diag = diag - diag % cfg.rerank_interval or diag
     marks, rr_us, pr_us, cp_us = [], [], [], []
     names = ("rerank_begin", "rerank_end", "recycle_end", "copies_end")
@@ -195,11 +210,11 @@ def main():
         "metric": "sparse decode attention effective HBM GB/s (% of peak) + rerank us/step",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 inputs, fp32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.batch, "context": max(cfg.ctx), "q_heads": cfg.num_q_heads,
                    "kv_heads": cfg.num_kv_heads, "stable_heads": int(sum(cfg.stable)), "topk_pages": cfg.max_topk,
                    "rerank_interval": cfg.rerank_interval, "pages_attended_per_step": cfg.pages_attended(),
-                   "promote_mode": args.promote_mode, "unstable_heads": "top-K every step" if args.paper_unstable_topk else "all pages", "attn_wavefronts": sess.ctx.cfg.attn_waves or "auto"},
+                   "promote_mode": args.promote_mode, "append_one_token_per_step": bool(args.append), "unstable_heads": "top-K every step" if args.paper_unstable_topk else "all pages", "attn_wavefronts": sess.ctx.cfg.attn_waves or "auto"},
         "pct_of_hbm_peak": round(100 * value / HBM_PEAK_GBS, 2),
         "attn_bytes_per_step": a_bytes, "rerank_bytes_per_invocation": r_bytes,
         "step_us_plain_median": round(float(np.median(plain_us)), 2) if plain_us else None,
@@ -215,7 +230,7 @@ def main():
         "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
         "overlap_rerank_with_unstable_heads": sess.overlap,
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None and not args.paper_unstable_topk else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
+                     "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None and not args.paper_unstable_topk and not args.append else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,
                      "event_bracket_us_raw": round(raw_ms * 1e3, 2), "event_bracket_us_empty_kernel": round(empty_ms * 1e3, 2),
                      "algorithmic_bytes_per_launch": int(bytes_per_launch)},

@@ -172,6 +172,11 @@ class DecodeSession:
     def append(self, k_bits: np.ndarray, v_bits: np.ndarray, append_mask=None):
         """One new token per sequence: page write, MinMax update, offload of pages that fill (library)."""
         kd, vd = self._bits_to_dev(k_bits), self._bits_to_dev(v_bits)
+        self.append_dev(kd, vd, append_mask)
+        self.torch.cuda.current_stream(self.dev).synchronize()   # kd / vd die with this frame
+
+    def append_dev(self, kd, vd, append_mask=None):
+        """Same, from bf16 device tensors [B, Hkv, D] the caller keeps alive."""
         self.ctx.fc_append_kv(k_new=kd, v_new=vd, context_lens=self.context_lens, block_table=self.block_table,
                               host_block_table=self.host_block_table, free_blocks=self.free_blocks,
                               free_count=self.free_count, resident_pages=self.resident_pages,
@@ -179,7 +184,6 @@ class DecodeSession:
                               num_pool_blocks=self.num_pool_blocks, host_pool=self.host_pool,
                               num_host_blocks=self.num_host_blocks, stable_flag=self.stable,
                               batch=self.cfg.batch, append_mask=append_mask, stream=self.main)
-        self.torch.cuda.current_stream(self.dev).synchronize()   # kd / vd die with this frame
 
     def rerank(self, rerank_mask=None, stream=None):
         self.ctx.fc_rerank_topk(q=self.q, minmax=self.minmax, context_lens=self.context_lens,
