@@ -20,7 +20,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per whole-pass attention launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same
-# counter reads for a copy kernel of known size (profiles/decode_hot_path_cfg2_llama8b_32k.md)
+# counter reads for a copy kernel of known size (fc_write_pages_kernel in the same run)
 MEASURED_TRAFFIC_BYTES = {"cfg2_llama8b_32k": 584.96e6}
 
 
@@ -109,7 +109,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards by sequence or KV head with no "
-              "exchange; see DESIGN.md); run with --gpus 1", file=sys.stderr)
+              "exchange between shards); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -144,7 +144,7 @@ def main():
             e = torch.cuda.Event(enable_timing=True)
             e.record(main)
             marks.append(e)
-        if new_kv is not None and (t > 0 or n_appended[0] > 0):   # the first step is the cold fill
+        if new_kv is not None and (t > 0 or n_appended[0] > 0):   # appends start after the cold fill: before it no page of a stable head, the partial last one included, is in HBM
             i = n_appended[0]
             sess.append_dev(new_kv[0][i], new_kv[1][i])
             n_appended[0] = i + 1

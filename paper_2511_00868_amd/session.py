@@ -67,7 +67,7 @@ def pool_blocks_needed(cfg: DecodeConfig) -> int:
 class DecodeSession:
     def __init__(self, cfg: DecodeConfig, wl: Workload, *, device: int = 0, attn_waves: int = 0,
                  promote_mode: int = binding.FC_PROMOTE_GATHER, keep_scores: bool = False,
-                 unstable_topk: bool = False):
+                 unstable_topk: bool = False, softmax_scale: float = 0.0):
         import torch
         self.torch = torch
         self.cfg, self.wl = cfg, wl
@@ -78,7 +78,8 @@ class DecodeSession:
         self.unstable_topk = unstable_topk
         B, H, Nmax, Kmax = cfg.batch, cfg.num_kv_heads, cfg.max_pages, list_capacity(cfg)
         self.ctx = binding.Context(num_q_heads=cfg.num_q_heads, num_kv_heads=H, max_batch=B,
-                                   max_pages_per_seq=Nmax, max_topk=Kmax, device=device, attn_waves=attn_waves)
+                                   max_pages_per_seq=Nmax, max_topk=Kmax, device=device, attn_waves=attn_waves,
+                                   softmax_scale=softmax_scale)
         order = wl.block_permutation(pool_blocks_needed(cfg))
         bt, hbt, fb, fc, nblk, nhost = plan_placement(cfg, order)
         self.num_pool_blocks, self.num_host_blocks = int(nblk), int(max(nhost, 2))
