@@ -190,3 +190,13 @@ def test_bulk_offload_copies_exact_pages_and_skips_bad_pairs():
         assert not got[41:].any() and not got[0].any()
     finally:
         s.close()
+
+
+@pytest.mark.timeout(900)
+def test_one_very_long_sequence_many_partials_per_item():
+    """262 147 tokens in one sequence: the unstable head alone is cut into ~1000 wavefront shares, so the
+    merge runs over several 256-partial chunks; K = 700 pages for the stable head."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.make_config(1, ctx=262144 + 3, steps=3), topk=(700,), hot_per_head=64,
+                              name="one_long_sequence")
+    _run(cfg)

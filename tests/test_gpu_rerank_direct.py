@@ -68,7 +68,7 @@ def test_all_scores_equal_selects_the_lowest_page_indices():
 
 
 @pytest.mark.parametrize("n,K", [(1, 1), (2, 1), (16, 16), (17, 3), (64, 64), (1000, 1), (1000, 999), (2048, 204),
-                                 (8192, 256)])
+                                 (8192, 256), (20000, 1500), (65536, 4096)])
 def test_quantised_scores_with_many_exact_ties(n, K):
     rng = np.random.default_rng(n * 7 + K)
     # few distinct integer rows -> few distinct scores -> long runs of exact ties across the K boundary
