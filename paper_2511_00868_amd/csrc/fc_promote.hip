@@ -37,6 +37,7 @@ struct fc_promote_params {
     long long num_pool_blocks, num_host_blocks;
     int32_t *copy_list;     // device or pinned: pairs (host block, pool block)
     int32_t *counters;      // device: [1] = error bits, [2 + parity] = pairs appended, [4] = workgroups done
+    int lds_lists;          // both page lists fit in dynamic LDS (2 * Kmax ints)
     int parity;             // calls alternate between two pair counters; each call clears the other one
     int32_t *host_total;    // pinned, may be NULL
     int32_t *host_total2;   // pinned scratch copy (memcpy mode reads it)
@@ -87,8 +88,18 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     n_old = min(max(n_old, 0), p.Kmax);
     n_new = min(max(n_new, 0), p.Kmax);
     n_free = min(max(n_free, 0), p.Kmax);
-    int32_t *old_l = p.resident_pages + item * (size_t)p.Kmax;
-    const int32_t *new_l = p.new_pages + item * (size_t)p.Kmax;
+    int32_t *old_g = p.resident_pages + item * (size_t)p.Kmax;
+    const int32_t *new_g = p.new_pages + item * (size_t)p.Kmax;
+    // both lists go to LDS when they fit: the binary searches below are chains of dependent reads
+    extern __shared__ int32_t lists[];
+    const bool in_lds = p.lds_lists != 0;
+    if (in_lds) {
+        for (int i = tid; i < n_old; i += FC_RECYCLE_THREADS) lists[i] = old_g[i];
+        for (int i = tid; i < n_new; i += FC_RECYCLE_THREADS) lists[p.Kmax + i] = new_g[i];
+        __syncthreads();
+    }
+    const int32_t *old_l = in_lds ? lists : old_g;
+    const int32_t *new_l = in_lds ? lists + p.Kmax : new_g;
     int32_t *tbl = p.block_table + item * (size_t)p.Nmax;
     const int32_t *htbl = p.host_block_table + item * (size_t)p.Nmax;
     int32_t *fb = p.free_blocks + item * (size_t)p.Kmax;
@@ -184,7 +195,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     }
     // 5. the new list becomes the resident list
     if (!skip) {
-        for (int i = tid; i < p.Kmax; i += FC_RECYCLE_THREADS) old_l[i] = i < n_new ? new_l[i] : -1;
+        for (int i = tid; i < p.Kmax; i += FC_RECYCLE_THREADS) old_g[i] = i < n_new ? new_l[i] : -1;
         if (tid == 0) {
             p.free_count[item] = left;
             p.resident_count[item] = n_new;
@@ -281,7 +292,9 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
         FC_HIP(ctx, hipStreamWaitEvent(ms, ctx->ev_copies_done, 0));
         ctx->copies_pending = false;
     }
-    hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), 0, ms, p);
+    const size_t list_bytes = 2 * (size_t)p.Kmax * sizeof(int32_t);
+    p.lds_lists = list_bytes <= 48 * 1024;
+    hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), p.lds_lists ? list_bytes : 0, ms, p);
     ++ctx->promote_calls;
     FC_HIP(ctx, hipGetLastError());
     FC_HIP(ctx, hipEventRecord(ctx->ev_diff_done, ms));

@@ -118,48 +118,51 @@ __device__ __forceinline__ uint32_t fc_order_key(float s)
 }
 
 constexpr int FC_SELECT_THREADS = 1024;
+constexpr int FC_SELECT_CACHED = 8;      // keys a thread keeps in registers: up to 8192 pages without re-reading
 
-__global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_params p)
+// CACHED: every thread holds the keys of pages tid + 1024 i (i < 8) in registers, so the four radix
+// passes and the compaction read the scores from memory once instead of five times.
+template <bool CACHED>
+__device__ __forceinline__ void fc_select_body(const fc_rerank_params &p, const float *score, int32_t *out, int n,
+                                               int want, int forced, int *hist, int (*wave_cnt)[FC_SELECT_THREADS / 64],
+                                               uint32_t *sh_prefix, int *sh_remaining)
 {
-    __shared__ int hist[256];
-    __shared__ int wave_cnt[2][FC_SELECT_THREADS / 64];
-    __shared__ uint32_t sh_prefix;
-    __shared__ int sh_remaining;
-
-    const int b = blockIdx.y;
-    if (p.rerank_mask && !p.rerank_mask[b]) return;
-    const int h = p.heads[blockIdx.x];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int ctx = p.context_lens[b];
-    int n = (ctx + FC_P - 1) / FC_P;
-    n = n > p.Nmax ? p.Nmax : (n < 0 ? 0 : n);
-    int K = p.k_per_seq[b];
-    K = K < 0 ? 0 : (K > p.Kmax ? p.Kmax : K);
-    const int want = K < n ? K : n;
-    const int forced = (ctx % FC_P != 0) ? n - 1 : -1;
-    const size_t item = (size_t)b * p.Hkv + h;
-    const float *score = p.scores + item * (size_t)p.Nmax;
-    int32_t *out = p.topk_pages + item * (size_t)p.Kmax;
-
     auto key_at = [&](int pg) -> uint32_t { return pg == forced ? 0xFFFFFFFFu : fc_order_key(score[pg]); };
+    uint32_t kreg[FC_SELECT_CACHED];
+    if (CACHED) {
+#pragma unroll
+        for (int i = 0; i < FC_SELECT_CACHED; ++i) {
+            const int pg = tid + i * FC_SELECT_THREADS;
+            kreg[i] = pg < n ? key_at(pg) : 0u;
+        }
+    }
 
     uint32_t T = 0;       // threshold key: pages with key > T are members
     int need_eq = n;      // how many pages with key == T are members (lowest indices first)
     if (want < n) {
-        if (tid == 0) { sh_prefix = 0; sh_remaining = want; }
+        if (tid == 0) { *sh_prefix = 0; *sh_remaining = want; }
         uint32_t mask = 0;
         for (int shift = 24; shift >= 0; shift -= 8) {
             if (tid < 256) hist[tid] = 0;
             __syncthreads();
-            const uint32_t prefix = sh_prefix;
-            for (int pg = tid; pg < n; pg += FC_SELECT_THREADS) {
-                const uint32_t k = key_at(pg);
-                if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+            const uint32_t prefix = *sh_prefix;
+            if (CACHED) {
+#pragma unroll
+                for (int i = 0; i < FC_SELECT_CACHED; ++i) {
+                    const uint32_t k = kreg[i];
+                    if (tid + i * FC_SELECT_THREADS < n && (k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+                }
+            } else {
+                for (int pg = tid; pg < n; pg += FC_SELECT_THREADS) {
+                    const uint32_t k = key_at(pg);
+                    if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+                }
             }
             __syncthreads();
             // suffix sums over the 256 digit counts by 256 threads: the digit whose suffix sum first
             // reaches `rem` holds the K-th largest key
-            const int rem = sh_remaining;
+            const int rem = *sh_remaining;
             int c = 0, x = 0;
             if (tid < 256) {
                 c = hist[255 - tid];
@@ -177,34 +180,29 @@ __global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_
                 for (int k = 0; k < wv; ++k) incl += wave_cnt[0][k];
                 const int excl = incl - c;
                 if (incl >= rem && excl < rem) {
-                    sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
-                    sh_remaining = rem - excl;
+                    *sh_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+                    *sh_remaining = rem - excl;
                 }
             }
             mask |= 0xFFu << shift;
             __syncthreads();
         }
-        T = sh_prefix;
-        need_eq = sh_remaining;
+        T = *sh_prefix;
+        need_eq = *sh_remaining;
     }
 
-    // index-ordered compaction
+    // index-ordered compaction, 1024 pages per round
     int eq_base = 0, sel_base = 0;
-    for (int base = 0; base < n; base += FC_SELECT_THREADS) {
-        const int pg = base + tid;
-        bool gt = false, eq = false;
-        if (pg < n) {
-            const uint32_t k = key_at(pg);
-            gt = k > T;
-            eq = k == T;
-        }
+    auto round = [&](int pg, uint32_t k) {
+        const bool live = pg < n;
+        const bool gt = live && k > T, eq = live && k == T;
         const unsigned long long beq = __ballot(eq);
         if (lane == 0) wave_cnt[0][wv] = __popcll(beq);
         __syncthreads();
         int eq_before = eq_base, eq_total = 0;
-        for (int k = 0; k < FC_SELECT_THREADS / 64; ++k) {
-            const int c = wave_cnt[0][k];
-            if (k < wv) eq_before += c;
+        for (int w = 0; w < FC_SELECT_THREADS / 64; ++w) {
+            const int c = wave_cnt[0][w];
+            if (w < wv) eq_before += c;
             eq_total += c;
         }
         eq_before += __popcll(beq & ((1ull << lane) - 1ull));
@@ -213,9 +211,9 @@ __global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_
         if (lane == 0) wave_cnt[1][wv] = __popcll(bsel);
         __syncthreads();
         int sel_before = sel_base, sel_total = 0;
-        for (int k = 0; k < FC_SELECT_THREADS / 64; ++k) {
-            const int c = wave_cnt[1][k];
-            if (k < wv) sel_before += c;
+        for (int w = 0; w < FC_SELECT_THREADS / 64; ++w) {
+            const int c = wave_cnt[1][w];
+            if (w < wv) sel_before += c;
             sel_total += c;
         }
         sel_before += __popcll(bsel & ((1ull << lane) - 1ull));
@@ -223,9 +221,45 @@ __global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_
         eq_base += eq_total;
         sel_base += sel_total;
         __syncthreads();
+    };
+    if (CACHED) {
+#pragma unroll
+        for (int i = 0; i < FC_SELECT_CACHED; ++i)
+            if (i * FC_SELECT_THREADS < n) round(tid + i * FC_SELECT_THREADS, kreg[i]);
+    } else {
+        for (int base = 0; base < n; base += FC_SELECT_THREADS) {
+            const int pg = base + tid;
+            round(pg, pg < n ? key_at(pg) : 0u);
+        }
     }
     for (int i = want + tid; i < p.Kmax; i += FC_SELECT_THREADS) out[i] = -1;
-    if (tid == 0) p.topk_count[item] = want;
+}
+
+__global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_params p)
+{
+    __shared__ int hist[256];
+    __shared__ int wave_cnt[2][FC_SELECT_THREADS / 64];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_remaining;
+
+    const int b = blockIdx.y;
+    if (p.rerank_mask && !p.rerank_mask[b]) return;
+    const int h = p.heads[blockIdx.x];
+    const int ctx = p.context_lens[b];
+    int n = (ctx + FC_P - 1) / FC_P;
+    n = n > p.Nmax ? p.Nmax : (n < 0 ? 0 : n);
+    int K = p.k_per_seq[b];
+    K = K < 0 ? 0 : (K > p.Kmax ? p.Kmax : K);
+    const int want = K < n ? K : n;
+    const int forced = (ctx % FC_P != 0) ? n - 1 : -1;
+    const size_t item = (size_t)b * p.Hkv + h;
+    const float *score = p.scores + item * (size_t)p.Nmax;
+    int32_t *out = p.topk_pages + item * (size_t)p.Kmax;
+    if (n <= FC_SELECT_CACHED * FC_SELECT_THREADS)
+        fc_select_body<true>(p, score, out, n, want, forced, hist, wave_cnt, &sh_prefix, &sh_remaining);
+    else
+        fc_select_body<false>(p, score, out, n, want, forced, hist, wave_cnt, &sh_prefix, &sh_remaining);
+    if (threadIdx.x == 0) p.topk_count[item] = want;
 }
 
 extern "C" int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *a, void *stream)
