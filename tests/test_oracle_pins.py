@@ -412,3 +412,18 @@ def test_stability_score_counts_and_classification_against_numpy():
     assert flags.sum() == 2 and flags[2] == 0
     # counts accumulate over samples
     np.testing.assert_array_equal(oracle.bottom_counts(ts, counts), 2 * counts)
+
+
+def test_ties_at_the_budget_boundary_go_to_the_lower_page_index():
+    assert list(oracle.select_topk(np.zeros(10), 160, 4)) == [0, 1, 2, 3]
+    s = np.array([1.0, 5.0, 1.0, 7.0, 1.0, 1.0, 0.5, 1.0])       # two clear winners, then a five-way tie for 2 seats
+    assert list(oracle.select_topk(s, 128, 4)) == [0, 1, 2, 3]
+    assert list(oracle.select_topk(s, 128, 5)) == [0, 1, 2, 3, 4]
+    assert list(oracle.select_topk(s, 125, 4)) == [0, 1, 3, 7]   # partial last page forced in: one tied seat left
+    rng = np.random.default_rng(2)
+    for _ in range(20):                                          # quantised scores: the boundary always cuts a tie group
+        n, K = int(rng.integers(5, 200)), int(rng.integers(1, 40))
+        s = rng.integers(0, 4, size=n).astype(np.float64)
+        got = oracle.select_topk(s, n * 16, K)
+        ref = sorted(np.lexsort((np.arange(n), -s))[:min(K, n)])
+        assert list(got) == ref
