@@ -105,6 +105,8 @@ def main():
     ap.add_argument("--append", action="store_true",
                     help="grow every context by one token per step (fc_append_kv: page write, MinMax update, offload on fill)")
     ap.add_argument("--no-overlap", action="store_true", help="run rerank, promotion and attention back to back on one stream")
+    ap.add_argument("--overlap-by", choices=["pages", "heads"], default="pages",
+                    help="how a rerank step's attention is split around the page copies")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -135,7 +137,7 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
-    sess.overlap = not args.no_overlap
+    sess.overlap = False if args.no_overlap else ("heads" if args.overlap_by == "heads" else True)
     main = torch.cuda.current_stream()
 
     def run_step(t, marks=None):
@@ -228,7 +230,7 @@ def main():
         "page_copies_us_per_invocation": round(float(np.median(cp_us)), 2) if cp_us else None,
         "rerank_invocations": n_rerank, "promoted_pages_last_rerank": promoted_last,
         "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
-        "overlap_rerank_with_unstable_heads": sess.overlap,
+        "rerank_step_overlap": "none" if not sess.overlap else ("by head class" if sess.overlap == "heads" else "by page (resident, then promoted)"),
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None and not args.paper_unstable_topk and not args.append else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,

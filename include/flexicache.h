@@ -167,6 +167,8 @@ typedef struct {
     int32_t batch;
     int32_t mode;                    /* FC_PROMOTE_GATHER | FC_PROMOTE_MEMCPY */
     int32_t *promoted_count;         /* dev out [batch][num_kv_heads] or NULL (0 for heads not touched) */
+    uint8_t *promoted_flags;         /* dev out [batch][num_kv_heads][Kmax] or NULL: 1 where resident_pages[..][i]
+                                        was promoted by this call (all 0 for sequences that did not rerank) */
     int32_t *total_promoted;         /* pinned out (one int32) or NULL: pages copied by this call;
                                         valid once side_stream has finished (at return for MEMCPY) */
 } fc_promote_args;
@@ -179,14 +181,16 @@ int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream
  *   lse = natural-log-sum-exp of the scaled logits (optional).
  * Every page of the set must be resident (block_table entry != 0).
  * head_subset splits one attention pass in two so that a caller that has just promoted pages can
- * overlap the copies with compute (Sec. 3.3 "Overlapping Transfer with Compute"):
- *   FC_HEADS_UNSTABLE  attends over the unstable heads only; it does not depend on the copies and does
- *                      not wait for them.  Its output rows are NOT yet written: they become valid with
- *   FC_HEADS_STABLE    which waits (on the GPU) for the copies, attends over the stable heads and then
- *                      writes the output rows of both classes (of the stable heads only, if no
- *                      FC_HEADS_UNSTABLE call preceded it on this context).
- *   FC_HEADS_ALL       everything in one pass. */
-enum { FC_HEADS_ALL = 0, FC_HEADS_UNSTABLE = 1, FC_HEADS_STABLE = 2 };
+ * overlap the copies with compute (Sec. 3.3 "Overlapping Transfer with Compute").  Two ways to split:
+ *   by page   FC_PAGES_RESIDENT attends over every head, leaving out the list entries that
+ *             promoted_flags marks as promoted by the last fc_promote_pages; it does not wait for the
+ *             copies.  FC_PAGES_PROMOTED then waits (on the GPU) for the copies, attends over exactly
+ *             those entries and writes all output rows.  Works for any mix of heads, all-stable included.
+ *   by head   FC_HEADS_UNSTABLE attends over the unstable heads only (no wait); FC_HEADS_STABLE waits for
+ *             the copies, attends over the stable heads and writes the output rows of both classes (of
+ *             the stable heads only, if no FC_HEADS_UNSTABLE call preceded it on this context).
+ * The output rows are complete only after the second call of a pair.  FC_HEADS_ALL: everything in one pass. */
+enum { FC_HEADS_ALL = 0, FC_HEADS_UNSTABLE = 1, FC_HEADS_STABLE = 2, FC_PAGES_RESIDENT = 3, FC_PAGES_PROMOTED = 4 };
 typedef struct {
     const void *q;               /* dev bf16 [batch][num_q_heads][D] */
     const void *kv_pool;         /* dev */
@@ -199,7 +203,9 @@ typedef struct {
     int32_t batch;
     float *out;                  /* dev out fp32 [batch][num_q_heads][D] */
     float *lse;                  /* dev out fp32 [batch][num_q_heads] or NULL */
-    int32_t head_subset;         /* FC_HEADS_ALL | FC_HEADS_UNSTABLE | FC_HEADS_STABLE */
+    int32_t head_subset;         /* FC_HEADS_ALL | FC_HEADS_UNSTABLE | FC_HEADS_STABLE | FC_PAGES_RESIDENT | FC_PAGES_PROMOTED */
+    const uint8_t *promoted_flags; /* dev [batch][num_kv_heads][Kmax], as written by fc_promote_pages; needed by
+                                      FC_PAGES_RESIDENT / FC_PAGES_PROMOTED, else may be NULL */
 } fc_attn_args;
 int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
 

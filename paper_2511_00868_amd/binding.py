@@ -12,7 +12,7 @@ LIB_PATH = os.environ.get("FLEXICACHE_LIB") or os.path.join(HERE, "libflexicache
 
 FC_OK, FC_ERR_INVALID_ARG, FC_ERR_UNSUPPORTED, FC_ERR_WORKSPACE, FC_ERR_HIP, FC_ERR_STATE = 0, -1, -2, -3, -4, -5
 FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY = 0, 1
-FC_HEADS_ALL, FC_HEADS_UNSTABLE, FC_HEADS_STABLE = 0, 1, 2
+FC_HEADS_ALL, FC_HEADS_UNSTABLE, FC_HEADS_STABLE, FC_PAGES_RESIDENT, FC_PAGES_PROMOTED = 0, 1, 2, 3, 4
 
 class fc_append_args(C.Structure):
     _fields_ = [("k_new", C.c_void_p), ("v_new", C.c_void_p), ("append_mask", C.c_void_p),
@@ -54,14 +54,15 @@ class fc_promote_args(C.Structure):
                 ("free_blocks", C.c_void_p), ("free_count", C.c_void_p), ("stable_flag", C.c_void_p),
                 ("rerank_mask", C.c_void_p), ("kv_pool", C.c_void_p), ("num_pool_blocks", C.c_int64),
                 ("host_pool", C.c_void_p), ("num_host_blocks", C.c_int64), ("batch", C.c_int32),
-                ("mode", C.c_int32), ("promoted_count", C.c_void_p), ("total_promoted", C.c_void_p)]
+                ("mode", C.c_int32), ("promoted_count", C.c_void_p), ("promoted_flags", C.c_void_p),
+                ("total_promoted", C.c_void_p)]
 
 
 class fc_attn_args(C.Structure):
     _fields_ = [("q", C.c_void_p), ("kv_pool", C.c_void_p), ("num_pool_blocks", C.c_int64),
                 ("block_table", C.c_void_p), ("context_lens", C.c_void_p), ("stable_flag", C.c_void_p),
                 ("topk_pages", C.c_void_p), ("topk_count", C.c_void_p), ("batch", C.c_int32),
-                ("out", C.c_void_p), ("lse", C.c_void_p), ("head_subset", C.c_int32)]
+                ("out", C.c_void_p), ("lse", C.c_void_p), ("head_subset", C.c_int32), ("promoted_flags", C.c_void_p)]
 
 
 _lib = None
@@ -189,21 +190,22 @@ class Context:
     def fc_promote_pages(self, *, new_pages, new_count, resident_pages, resident_count, block_table,
                          host_block_table, free_blocks, free_count, stable_flag, kv_pool, num_pool_blocks: int,
                          host_pool, num_host_blocks: int, batch: int, main_stream, side_stream,
-                         mode: int = FC_PROMOTE_GATHER, rerank_mask=None, promoted_count=None, total_promoted=None):
+                         mode: int = FC_PROMOTE_GATHER, rerank_mask=None, promoted_count=None, promoted_flags=None,
+                         total_promoted=None):
         flags = _host_u8(stable_flag)
         a = fc_promote_args(_ptr(new_pages), _ptr(new_count), _ptr(resident_pages), _ptr(resident_count),
                             _ptr(block_table), _ptr(host_block_table), _ptr(free_blocks), _ptr(free_count),
                             C.addressof(flags), _ptr(rerank_mask), _ptr(kv_pool), num_pool_blocks, _ptr(host_pool),
-                            num_host_blocks, batch, mode, _ptr(promoted_count), _ptr(total_promoted))
+                            num_host_blocks, batch, mode, _ptr(promoted_count), _ptr(promoted_flags), _ptr(total_promoted))
         self._check(self.lib.fc_promote_pages(self.handle, C.byref(a), self._stream(main_stream),
                                               self._stream(side_stream)))
 
     def fc_sparse_decode_attn(self, *, q, kv_pool, num_pool_blocks: int, block_table, context_lens, stable_flag,
                               topk_pages, topk_count, batch: int, out, lse=None, head_subset: int = FC_HEADS_ALL,
-                              stream=None):
+                              promoted_flags=None, stream=None):
         flags = _host_u8(stable_flag)
         a = fc_attn_args(_ptr(q), _ptr(kv_pool), num_pool_blocks, _ptr(block_table), _ptr(context_lens),
-                         C.addressof(flags), _ptr(topk_pages), _ptr(topk_count), batch, _ptr(out), _ptr(lse), head_subset)
+                         C.addressof(flags), _ptr(topk_pages), _ptr(topk_count), batch, _ptr(out), _ptr(lse), head_subset, _ptr(promoted_flags))
         self._check(self.lib.fc_sparse_decode_attn(self.handle, C.byref(a), self._stream(stream)))
 
     def fc_append_kv(self, *, k_new, v_new, context_lens, block_table, host_block_table, free_blocks, free_count,

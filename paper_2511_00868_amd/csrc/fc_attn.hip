@@ -50,6 +50,9 @@ struct fc_attn_params {
     int32_t *seg_start;   // [2][max_items + 2]: per schedule the prefix sums, then pages per wavefront
     int sched;            // schedule / partial-slot set this attention launch writes (0 or 1)
     int sched_unstable, sched_stable;   // which set the merge reads for each class of head
+    int stable_both_sets;  // merge: a stable item has partials in set 0 (resident pages) and set 1 (promoted pages)
+    int page_filter;       // 0: every page; 1: skip list entries flagged as just promoted; 2: only those
+    const uint8_t *promoted_flags;   // [batch][Hkv][Kmax], parallel to topk_pages (page_filter != 0)
     int sched_stride, slot_stride;
     float *part_ml;
     float *part_acc;
@@ -155,7 +158,7 @@ __device__ __forceinline__ void fc_store_final(const fc_attn_params &p, size_t r
     }
 }
 
-// SUBSET only names the launch (FC_HEADS_ALL / _UNSTABLE / _STABLE) so that profilers list the three kinds
+// SUBSET only names the launch (FC_HEADS_ALL ... FC_PAGES_PROMOTED) so that profilers list the kinds
 // of launch, which move very different numbers of bytes, under separate kernel names.
 #ifndef FC_ATTN_MIN_WAVES_PER_SIMD
 #define FC_ATTN_MIN_WAVES_PER_SIMD 2
@@ -271,19 +274,24 @@ __global__ __launch_bounds__(256, FC_ATTN_MIN_WAVES_PER_SIMD) void fc_decode_att
                 blk = blk < 0 ? 0 : (blk >= p.num_blocks ? p.num_blocks - 1 : blk);
                 blk_v = (int)blk;
                 ntok_v = logical == last_page ? last_ntok : FC_P;
+                if (p.page_filter != 0) {     // 0 valid tokens = this call leaves the page to its partner call
+                    const bool fresh = stable && p.promoted_flags[(size_t)item * p.Kmax + base + lane] != 0;
+                    if ((p.page_filter == 1) == fresh) ntok_v = 0;
+                }
             }
             fc_page_regs buf[FC_ATTN_NBUF];
 #pragma unroll
             for (int i = 0; i < FC_ATTN_NBUF; ++i)
-                if (i < cnt) fc_load_page(buf[i], p.pool, __builtin_amdgcn_readlane(blk_v, i), lane_k_off, lane_v_off);
+                if (i < cnt && __builtin_amdgcn_readlane(ntok_v, i) > 0)
+                    fc_load_page(buf[i], p.pool, __builtin_amdgcn_readlane(blk_v, i), lane_k_off, lane_v_off);
             for (int t0 = 0; t0 < cnt; t0 += FC_ATTN_NBUF) {
 #pragma unroll
                 for (int i = 0; i < FC_ATTN_NBUF; ++i) {
                     const int t = t0 + i;
                     if (t < cnt) {
                         const int ntok = __builtin_amdgcn_readlane(ntok_v, t);
-                        fc_consume_page(st, buf[i], qb, ntok, j, p.scale_log2);
-                        if (t + FC_ATTN_NBUF < cnt)
+                        if (ntok > 0) fc_consume_page(st, buf[i], qb, ntok, j, p.scale_log2);
+                        if (t + FC_ATTN_NBUF < cnt && __builtin_amdgcn_readlane(ntok_v, t + FC_ATTN_NBUF) > 0)
                             fc_load_page(buf[i], p.pool, __builtin_amdgcn_readlane(blk_v, t + FC_ATTN_NBUF),
                                          lane_k_off, lane_v_off);
                     }
@@ -296,7 +304,7 @@ __global__ __launch_bounds__(256, FC_ATTN_MIN_WAVES_PER_SIMD) void fc_decode_att
 
         const size_t row = (size_t)b * p.Hq + (size_t)h * p.G;
         const int w_first = s0 / L, w_last = (s1 - 1) / L;
-        if (w_first == w_last) {
+        if (w_first == w_last && !(stable && p.page_filter != 0)) {
             fc_store_final(p, row, n, j, st.m, l, st.acc);           // this wavefront saw the whole item
         } else {
             const int slot = p.sched * p.slot_stride + w + item;
@@ -328,23 +336,45 @@ __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
     const int items = p.batch * p.Hkv;
     const int b = item / p.Hkv, h = item - b * p.Hkv;
     if (!((p.active_mask >> h) & 1ull)) return;   // not covered by this call: rows stay as they are
-    const int sched = ((p.stable_mask >> h) & 1ull) ? p.sched_stable : p.sched_unstable;
-    const int32_t *seg = p.seg_start + (size_t)sched * p.sched_stride;
-    const int s0 = seg[item], s1 = seg[item + 1], L = seg[items + 1];
+    const bool stable = (p.stable_mask >> h) & 1ull;
     const size_t row = (size_t)b * p.Hq + (size_t)h * p.G + g;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    if (s1 <= s0) {   // an item without pages: defined output
+    // up to two runs of partials: [slot_a, slot_a + n_a) and [slot_b, slot_b + n_b)
+    size_t slot_a = 0, slot_b = 0;
+    int n_a = 0, n_b = 0;
+    bool any_pages = false, direct = false;
+    {
+        const int sched = stable ? (p.stable_both_sets ? 0 : p.sched_stable) : p.sched_unstable;
+        const int32_t *seg = p.seg_start + (size_t)sched * p.sched_stride;
+        const int s0 = seg[item], s1 = seg[item + 1], L = seg[items + 1];
+        if (s1 > s0) {
+            any_pages = true;
+            const int w_first = s0 / L, w_last = (s1 - 1) / L;
+            direct = w_first == w_last && !(stable && p.stable_both_sets);
+            n_a = w_last - w_first + 1;
+            slot_a = (size_t)sched * p.slot_stride + item + w_first;
+        }
+    }
+    if (stable && p.stable_both_sets) {
+        const int32_t *seg = p.seg_start + (size_t)p.sched_stride;
+        const int s0 = seg[item], s1 = seg[item + 1], L = seg[items + 1];
+        if (s1 > s0) {
+            const int w_first = s0 / L, w_last = (s1 - 1) / L;
+            n_b = w_last - w_first + 1;
+            slot_b = (size_t)p.slot_stride + item + w_first;
+        }
+    }
+    if (!any_pages) {   // an item without pages: defined output
         if (tid < FC_D) p.out[row * FC_D + tid] = 0.f;
         if (p.lse && tid == 0) p.lse[row] = -INFINITY;
         return;
     }
-    const int w_first = s0 / L, w_last = (s1 - 1) / L;
-    if (w_first == w_last) return;            // written directly by the attention kernel
-    const int n_parts = w_last - w_first + 1;
-    const size_t slot0 = (size_t)sched * p.slot_stride + item + w_first;
+    if (direct) return;                       // written directly by the attention kernel
+    const int n_parts = n_a + n_b;
+    auto slot_of = [&](int i) -> size_t { return i < n_a ? slot_a + i : slot_b + (i - n_a); };
 
     float mstar = -INFINITY;
-    for (int i = tid; i < n_parts; i += 256) mstar = fmaxf(mstar, p.part_ml[((slot0 + i) * 16 + g) * 2]);
+    for (int i = tid; i < n_parts; i += 256) mstar = fmaxf(mstar, p.part_ml[(slot_of(i) * 16 + g) * 2]);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, d));
     if (lane == 0) red[wv] = mstar;
@@ -358,16 +388,15 @@ __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
     for (int base = 0; base < n_parts; base += 256) {
         const int cnt = min(256, n_parts - base);
         if (tid < cnt) {
-            const float *ml = p.part_ml + ((slot0 + base + tid) * 16 + g) * 2;
-            const float wt = __builtin_amdgcn_exp2f(ml[0] - mstar);
+            const float *ml = p.part_ml + (slot_of(base + tid) * 16 + g) * 2;
+            const float wt = ml[0] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml[0] - mstar);   // a share with no page
             wts[tid] = wt;
             lsum += wt * ml[1];
         }
         __syncthreads();
-        const float *src = p.part_acc + ((slot0 + base) * p.G + g) * FC_D + 4 * d4;
 #pragma unroll 8
         for (int k = sub; k < cnt; k += 8)
-            acc += wts[k] * *reinterpret_cast<const float4_t *>(src + (size_t)k * p.G * FC_D);
+            acc += wts[k] * *reinterpret_cast<const float4_t *>(p.part_acc + (slot_of(base + k) * p.G + g) * FC_D + 4 * d4);
         __syncthreads();
     }
 #pragma unroll
@@ -393,7 +422,8 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
                "fc_sparse_decode_attn: NULL pointer among q, kv_pool, block_table, context_lens, stable_flag, out");
     FC_REQUIRE(ctx, a->batch >= 1 && a->batch <= ctx->cfg.max_batch, "fc_sparse_decode_attn: batch=%d outside 1..%d", a->batch, ctx->cfg.max_batch);
     FC_REQUIRE(ctx, a->num_pool_blocks >= 2, "fc_sparse_decode_attn: num_pool_blocks must be >= 2");
-    FC_REQUIRE(ctx, a->head_subset >= FC_HEADS_ALL && a->head_subset <= FC_HEADS_STABLE, "fc_sparse_decode_attn: unknown head_subset %d", a->head_subset);
+    FC_REQUIRE(ctx, a->head_subset >= FC_HEADS_ALL && a->head_subset <= FC_PAGES_PROMOTED, "fc_sparse_decode_attn: unknown head_subset %d", a->head_subset);
+    FC_REQUIRE(ctx, a->head_subset < FC_PAGES_RESIDENT || a->promoted_flags, "fc_sparse_decode_attn: FC_PAGES_RESIDENT / FC_PAGES_PROMOTED need promoted_flags");
     const uint64_t mask = fc_stable_mask(ctx->cfg, a->stable_flag);
     FC_REQUIRE(ctx, mask == 0 || (a->topk_pages && a->topk_count), "fc_sparse_decode_attn: stable heads need topk_pages and topk_count");
     hipStream_t s = (hipStream_t)stream;
@@ -408,12 +438,16 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     p.topk_count = a->topk_count ? a->topk_count : a->context_lens;
     p.stable_mask = mask;
     const uint64_t all = ctx->cfg.num_kv_heads == 64 ? ~0ull : ((1ull << ctx->cfg.num_kv_heads) - 1);
-    p.active_mask = a->head_subset == FC_HEADS_UNSTABLE ? (all & ~mask) : a->head_subset == FC_HEADS_STABLE ? mask : all;
-    // FC_HEADS_UNSTABLE leaves its partials in set 0 and defers the merge; the FC_HEADS_STABLE call that
-    // follows writes set 1 and merges both classes in one kernel.
-    p.sched = a->head_subset == FC_HEADS_STABLE ? 1 : 0;
+    const int sub = a->head_subset;
+    p.active_mask = sub == FC_HEADS_UNSTABLE ? (all & ~mask) : (sub == FC_HEADS_STABLE || sub == FC_PAGES_PROMOTED) ? mask : all;
+    // A first call of a pair (FC_HEADS_UNSTABLE or FC_PAGES_RESIDENT) leaves its partials in set 0 and
+    // defers the merge; the second (FC_HEADS_STABLE or FC_PAGES_PROMOTED) writes set 1 and merges both.
+    p.sched = (sub == FC_HEADS_STABLE || sub == FC_PAGES_PROMOTED) ? 1 : 0;
     p.sched_unstable = 0;
     p.sched_stable = p.sched;
+    p.stable_both_sets = sub == FC_PAGES_PROMOTED ? 1 : 0;
+    p.page_filter = sub == FC_PAGES_RESIDENT ? 1 : sub == FC_PAGES_PROMOTED ? 2 : 0;
+    p.promoted_flags = a->promoted_flags;
     p.sched_stride = ctx->max_items + 2;
     p.slot_stride = ctx->slots;
     p.batch = a->batch;
@@ -430,12 +464,17 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     p.out = a->out;
     p.lse = a->lse;
 
-    const bool merge_now = a->head_subset != FC_HEADS_UNSTABLE;
+    const bool first_of_pair = sub == FC_HEADS_UNSTABLE || sub == FC_PAGES_RESIDENT;
+    const bool merge_now = !first_of_pair;
     uint64_t merge_mask = p.active_mask;
-    if (a->head_subset == FC_HEADS_UNSTABLE) ctx->unstable_pending = true;
-    if (a->head_subset == FC_HEADS_STABLE && ctx->unstable_pending) merge_mask = all;
-    if (merge_now) ctx->unstable_pending = false;
-    if (ctx->copies_pending && (p.active_mask & mask)) {   // promoted pages still in flight on the side stream
+    if (sub == FC_PAGES_PROMOTED) {
+        FC_REQUIRE(ctx, ctx->pending_pair == FC_PAGES_RESIDENT, "fc_sparse_decode_attn: FC_PAGES_PROMOTED must follow FC_PAGES_RESIDENT");
+        merge_mask = all;
+    }
+    if (sub == FC_HEADS_STABLE && ctx->pending_pair == FC_HEADS_UNSTABLE) merge_mask = all;
+    ctx->pending_pair = first_of_pair ? sub : 0;
+    const bool needs_copies = sub != FC_HEADS_UNSTABLE && sub != FC_PAGES_RESIDENT && (p.active_mask & mask);
+    if (ctx->copies_pending && needs_copies) {   // promoted pages still in flight on the side stream
         FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_copies_done, 0));
         ctx->copies_pending = false;
     }
@@ -445,9 +484,11 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
         if (prof) prof = (ctx->prof_seen++ % ctx->prof_stride) == 0;
         if (prof) FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used], s));
         const dim3 grid(p.n_waves / 4), block(256);
-        if (a->head_subset == FC_HEADS_ALL) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_ALL>, grid, block, 0, s, p);
-        else if (a->head_subset == FC_HEADS_UNSTABLE) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_UNSTABLE>, grid, block, 0, s, p);
-        else hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_STABLE>, grid, block, 0, s, p);
+        if (sub == FC_HEADS_ALL) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_ALL>, grid, block, 0, s, p);
+        else if (sub == FC_HEADS_UNSTABLE) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_UNSTABLE>, grid, block, 0, s, p);
+        else if (sub == FC_HEADS_STABLE) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_STABLE>, grid, block, 0, s, p);
+        else if (sub == FC_PAGES_RESIDENT) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_PAGES_RESIDENT>, grid, block, 0, s, p);
+        else hipLaunchKernelGGL(fc_decode_attn_kernel<FC_PAGES_PROMOTED>, grid, block, 0, s, p);
         if (prof) {
             FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used + 1], s));
             ++ctx->prof_used;

@@ -153,7 +153,7 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
         return FC_ERR_HIP;
     }
     c->copies_pending = false;
-    c->unstable_pending = false;
+    c->pending_pair = 0;
     c->promote_calls = 0;
     c->gather_blocks = 32;
     if (const char *env = getenv("FC_GATHER_BLOCKS")) {

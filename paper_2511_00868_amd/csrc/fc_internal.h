@@ -49,7 +49,7 @@ struct fc_ctx {
     hipEvent_t ev_diff_done;
     hipEvent_t ev_copies_done;
     bool copies_pending;
-    bool unstable_pending;   // an FC_HEADS_UNSTABLE call has left partials that the next FC_HEADS_STABLE call merges
+    int pending_pair;        // FC_HEADS_UNSTABLE or FC_PAGES_RESIDENT has left partials for its partner call to merge, else 0
     unsigned promote_calls;
     int gather_threads;   // threads per gather workgroup (64, 128 or 256)
     int gather_blocks;    // workgroups of the host->HBM gather kernel (few and small: see fc_promote.hip)

@@ -32,6 +32,7 @@ struct fc_promote_params {
     int32_t *free_count;
     const uint8_t *rerank_mask;
     int32_t *promoted_count;
+    uint8_t *promoted_flags;
     int batch, Hkv, Nmax, Kmax, n_stable;
     uint8_t heads[64];
     long long num_pool_blocks, num_host_blocks;
@@ -156,6 +157,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
         }
         int tot;
         const int r = taken + fc_block_rank(pr, wave_cnt, tot);
+        if (p.promoted_flags && i < n_new) p.promoted_flags[item * (size_t)p.Kmax + i] = pr ? 1 : 0;
         if (pr) {
             if (r < pool) {
                 long long blk = fb[r];
@@ -193,6 +195,8 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
         if (i < left) fb[i] = v;
         __syncthreads();
     }
+    if (p.promoted_flags)      // entries past the list, and whole lists of sequences that did not rerank, are not promoted
+        for (int i = (skip ? 0 : n_new) + tid; i < p.Kmax; i += FC_RECYCLE_THREADS) p.promoted_flags[item * (size_t)p.Kmax + i] = 0;
     // 5. the new list becomes the resident list
     if (!skip) {
         for (int i = tid; i < p.Kmax; i += FC_RECYCLE_THREADS) old_g[i] = i < n_new ? new_l[i] : -1;
@@ -262,6 +266,7 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     p.free_count = a->free_count;
     p.rerank_mask = a->rerank_mask;
     p.promoted_count = a->promoted_count;
+    p.promoted_flags = a->promoted_flags;
     p.batch = a->batch;
     p.Hkv = ctx->cfg.num_kv_heads;
     p.Nmax = ctx->cfg.max_pages_per_seq;

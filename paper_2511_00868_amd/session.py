@@ -100,6 +100,7 @@ class DecodeSession:
         self.resident_pages = torch.full((B, H, Kmax), -1, **i32)
         self.resident_count = torch.zeros((B, H), **i32)
         self.promoted_count = torch.zeros((B, H), **i32)
+        self.promoted_flags = torch.zeros((B, H, Kmax), dtype=torch.uint8, device=self.dev)
         self.total_promoted = torch.zeros(1, dtype=torch.int32, pin_memory=True)
         self.scores = torch.zeros((B, H, Nmax), dtype=torch.float32, device=self.dev) if keep_scores else None
         self.q = torch.zeros((B, cfg.num_q_heads, 128), dtype=torch.bfloat16, device=self.dev)
@@ -210,7 +211,8 @@ class DecodeSession:
                                   num_host_blocks=self.num_host_blocks, batch=self.cfg.batch,
                                   main_stream=stream or self.main, side_stream=copy_stream or self.copy,
                                   mode=self.promote_mode, rerank_mask=rerank_mask,
-                                  promoted_count=self.promoted_count, total_promoted=self.total_promoted)
+                                  promoted_count=self.promoted_count, promoted_flags=self.promoted_flags,
+                                  total_promoted=self.total_promoted)
 
     def attend(self, head_subset: int = binding.FC_HEADS_ALL):
         listed = [True] * len(self.stable) if self.unstable_topk else self.stable
@@ -218,15 +220,17 @@ class DecodeSession:
                                        block_table=self.block_table, context_lens=self.context_lens,
                                        stable_flag=listed, topk_pages=self.resident_pages,
                                        topk_count=self.resident_count, batch=self.cfg.batch, out=self.out,
-                                       lse=self.lse, head_subset=head_subset, stream=self.main)
+                                       lse=self.lse, head_subset=head_subset, promoted_flags=self.promoted_flags,
+                                       stream=self.main)
 
     def step(self, t: int):
         """One pass of the hot path for decode step t (queries already set on the main stream).
 
         On a rerank step scoring, selection and block recycling run first; the page copies then go
-        to the copy stream while the main stream attends over the unstable heads, which need none of
-        them; the stable heads follow once the copies have landed (the library makes that call wait,
-        on the GPU, for the copies)."""
+        to the copy stream while the main stream attends over everything that is already in HBM
+        (all pages of unstable heads, the kept pages of stable heads); the promoted pages follow once
+        the copies have landed (the library makes that call wait, on the GPU, for the copies).
+        `overlap = "heads"` splits by head class instead, `overlap = False` does not split."""
         if self.unstable_topk:
             if not all(self.stable):
                 self.rerank_unstable()
@@ -254,9 +258,13 @@ class DecodeSession:
             if ev is not None:
                 ev["recycle_end"].record(self.main)
                 ev["copies_end"].record(self.copy)
-            if self.overlap and not all(self.stable):
+            if self.overlap == "heads" and not all(self.stable):
                 self.attend(binding.FC_HEADS_UNSTABLE)
                 self.attend(binding.FC_HEADS_STABLE)
+                return
+            if self.overlap:
+                self.attend(binding.FC_PAGES_RESIDENT)
+                self.attend(binding.FC_PAGES_PROMOTED)
                 return
         self.attend()
 

@@ -68,6 +68,6 @@ def test_create_rejects_null_and_small_buffers():
 def test_struct_sizes_match_the_c_layout():
     assert C.sizeof(binding.fc_config) == 40
     assert C.sizeof(binding.fc_rerank_args) == 80
-    assert C.sizeof(binding.fc_attn_args) == 96
-    assert C.sizeof(binding.fc_promote_args) == 136
+    assert C.sizeof(binding.fc_attn_args) == 104
+    assert C.sizeof(binding.fc_promote_args) == 144
     assert C.sizeof(binding.fc_append_args) == 136

@@ -200,3 +200,11 @@ def test_one_very_long_sequence_many_partials_per_item():
     cfg = dataclasses.replace(synth.make_config(1, ctx=262144 + 3, steps=3), topk=(700,), hot_per_head=64,
                               name="one_long_sequence")
     _run(cfg)
+
+
+@pytest.mark.parametrize("overlap", ["heads", False])
+def test_other_ways_of_running_a_rerank_step(overlap):
+    """The default splits a rerank step by page (resident, then promoted); splitting by head class and
+    not splitting at all must give the same results."""
+    _run(synth.make_config(5, batch=3, ctx=8192, steps=9), overlap=overlap)
+    _run(synth.make_config(2, batch=2, ctx=4096 + 7, steps=5), overlap=overlap)
