@@ -40,7 +40,11 @@
  *   topk_pages   int32 [batch][num_kv_heads][Kmax]: ascending logical page ids, -1 padded
  *   topk_count   int32 [batch][num_kv_heads]
  *   context_lens int32 [batch]: tokens in the sequence, >= 1; pages = ceil(len / 16) <= Nmax
- *   stable_flag  uint8 [num_kv_heads] on the HOST: 1 = stable head (profiled offline, Sec. 2.3)
+ *   stable_flag  uint8 [num_kv_heads] on the HOST: 1 = stable head (profiled offline, Sec. 2.3).  For
+ *                fc_rerank_topk it names the heads to rescore; for fc_sparse_decode_attn the heads that
+ *                attend over their list instead of over all pages (the paper's own variant, in which the
+ *                unstable heads also attend over a top-K list that is rescored every step, sets it for
+ *                every head there and calls fc_rerank_topk for the unstable heads at every step)
  */
 #ifndef FLEXICACHE_H
 #define FLEXICACHE_H
