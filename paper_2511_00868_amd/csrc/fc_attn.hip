@@ -129,14 +129,16 @@ __device__ __forceinline__ void fc_consume_page(fc_softmax_state &st, fc_page_re
 #pragma unroll
         for (int c = 0; c < 8; ++c) st.acc[c] *= alpha;
     }
-    // P = hi + lo, both bf16 (truncation: hi keeps the top 8 mantissa bits, lo the next 8)
+    // P = hi + lo, both bf16: hi is P truncated to 8 mantissa bits, lo the remainder (exact in fp32)
+    // rounded to nearest, so P is carried with a relative error of at most 2^-17
     short4_t ph, pl;
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const uint32_t u = __float_as_uint(pr[v]);
         const float hi = __uint_as_float(u & 0xFFFF0000u);
+        const uint32_t r = __float_as_uint(pr[v] - hi);
         ph[v] = (short)(u >> 16);
-        pl[v] = (short)(__float_as_uint(pr[v] - hi) >> 16);
+        pl[v] = (short)((r + 0x7FFFu + ((r >> 16) & 1u)) >> 16);
     }
 #pragma unroll
     for (int c = 0; c < 8; ++c) {

@@ -240,6 +240,8 @@ class ParityRun:
         self.check_minmax()
         for t in range(steps or self.cfg.steps):
             self.step(t)
+        print(f"[{self.cfg.name}] worst attention error {self.worst:.2e}, promoted {self.promoted_total}, "
+              f"near-tie swaps {self.near_tie_swaps}")
         return self
 
     def close(self):
