@@ -128,11 +128,11 @@ def main():
     wl = synth.Workload(cfg)
     mode = binding.FC_PROMOTE_GATHER if args.promote_mode == "gather" else binding.FC_PROMOTE_MEMCPY
     sess = DecodeSession(cfg, wl, promote_mode=mode, attn_waves=args.attn_waves, unstable_topk=args.paper_unstable_topk)
-    q_all = torch.stack([sess._bits_to_dev(wl.queries(t)) for t in range(total_steps)])
+    q_all = torch.stack([sess.bits_to_dev(wl.queries(t)) for t in range(total_steps)])
     new_kv = None
     if args.append:
         toks = [wl.append(t) for t in range(total_steps + diag_steps)]
-        new_kv = (torch.stack([sess._bits_to_dev(k) for k, _ in toks]), torch.stack([sess._bits_to_dev(v) for _, v in toks]))
+        new_kv = (torch.stack([sess.bits_to_dev(k) for k, _ in toks]), torch.stack([sess.bits_to_dev(v) for _, v in toks]))
     n_appended = [0]
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen

@@ -31,7 +31,7 @@ def layer_config(batch: int, ctx: int, budget_pages: int, R: int, dense: bool) -
 def time_steps(sess: DecodeSession, wl: synth.Workload, steps: int, warm: int, fn) -> float:
     """Mean microseconds per step of fn(t) over `steps` steps after `warm` warm-up steps."""
     import torch
-    qs = [sess._bits_to_dev(wl.queries(t)) for t in range(warm + steps)]
+    qs = [sess.bits_to_dev(wl.queries(t)) for t in range(warm + steps)]
     for t in range(warm):
         sess.q = qs[t]
         fn(t)

@@ -116,7 +116,7 @@ class DecodeSession:
         torch.cuda.synchronize(self.dev)
 
     # ---- placement of page contents ---------------------------------------------------------------
-    def _bits_to_dev(self, a: np.ndarray):
+    def bits_to_dev(self, a: np.ndarray):
         return self.torch.from_numpy(a.view(np.int16)).to(self.dev).view(self.torch.bfloat16)
 
     def _write_sequence(self, b: int, only: Optional[Dict[int, Sequence[int]]]):
@@ -124,8 +124,8 @@ class DecodeSession:
         torch, cfg = self.torch, self.cfg
         cur = self.wl.cur_len[b]
         n = -(-cur // 16)
-        kd = self._bits_to_dev(np.ascontiguousarray(self.wl.k[b][:, :n * 16]))
-        vd = self._bits_to_dev(np.ascontiguousarray(self.wl.v[b][:, :n * 16]))
+        kd = self.bits_to_dev(np.ascontiguousarray(self.wl.k[b][:, :n * 16]))
+        vd = self.bits_to_dev(np.ascontiguousarray(self.wl.v[b][:, :n * 16]))
         sel = np.zeros((cfg.num_kv_heads, n), dtype=bool)
         if only is None:
             sel[:] = True
@@ -169,11 +169,11 @@ class DecodeSession:
 
     # ---- the three hot-path calls -------------------------------------------------------------------
     def set_queries(self, q_bits: np.ndarray):
-        self.q.copy_(self._bits_to_dev(q_bits))
+        self.q.copy_(self.bits_to_dev(q_bits))
 
     def append(self, k_bits: np.ndarray, v_bits: np.ndarray, append_mask=None):
         """One new token per sequence: page write, MinMax update, offload of pages that fill (library)."""
-        kd, vd = self._bits_to_dev(k_bits), self._bits_to_dev(v_bits)
+        kd, vd = self.bits_to_dev(k_bits), self.bits_to_dev(v_bits)
         self.append_dev(kd, vd, append_mask)
         self.torch.cuda.current_stream(self.dev).synchronize()   # kd / vd die with this frame
 
