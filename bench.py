@@ -199,6 +199,11 @@ def main():
     plain_us = [u for u, r in zip(step_us, is_rer) if not r]
     promoted_last = int(sess.total_promoted[0])
 
+    # same-box ceiling: a plain streaming read of as many bytes of the pool as one attention call moves
+    pool_bytes = sess.kv_pool.numel() * sess.kv_pool.element_size()
+    ceil_bytes = min(pool_bytes, attention_bytes(cfg, args.paper_unstable_topk)) // 4096 * 4096
+    ceil_gbs, ceil_us = sess.ctx.fc_measure_stream_read(sess.kv_pool, ceil_bytes, 16, main)
+
     n_rerank = sum(is_rer_timed)
     a_bytes, r_bytes = attention_bytes(cfg, args.paper_unstable_topk), rerank_bytes(cfg)
     step_bytes = a_bytes * args.steps + r_bytes * n_rerank
@@ -221,6 +226,8 @@ def main():
         "attn_bytes_per_step": a_bytes, "rerank_bytes_per_invocation": r_bytes,
         "step_us_plain_median": round(float(np.median(plain_us)), 2) if plain_us else None,
         "step_us_rerank_median": round(float(np.median(rer_us)), 2) if rer_us else None,
+        "step_us_plain_min": round(float(np.min(plain_us)), 2) if plain_us else None,
+        "step_us_rerank_min": round(float(np.min(rer_us)), 2) if rer_us else None,
         "rerank_exposed_us_per_step_amortised": round((float(np.median(rer_us)) - float(np.median(plain_us)))
                                                       / cfg.rerank_interval, 2) if rer_us and plain_us else None,
         "attn_call_GBps_plain_step": round(a_bytes / (float(np.median(plain_us)) * 1e-6) / 1e9, 1) if plain_us else None,
@@ -235,7 +242,10 @@ def main():
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None and not args.paper_unstable_topk and not args.append else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,
                      "event_bracket_us_raw": round(raw_ms * 1e3, 2), "event_bracket_us_empty_kernel": round(empty_ms * 1e3, 2),
-                     "algorithmic_bytes_per_launch": int(bytes_per_launch)},
+                     "algorithmic_bytes_per_launch": int(bytes_per_launch),
+                     "stream_read_ceiling_GBps": round(ceil_gbs, 1), "stream_read_ceiling_us": round(ceil_us, 2),
+                     "stream_read_ceiling_bytes": int(ceil_bytes),
+                     "frac_of_stream_read_ceiling": round(ach / ceil_gbs, 4) if ceil_gbs > 0 else None},
         "setup_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:

@@ -296,6 +296,16 @@ int fc_check_device_state(fc_ctx *ctx, void *stream);
 int fc_profile_begin(fc_ctx *ctx, int32_t every_nth, void *stream);
 int fc_profile_end(fc_ctx *ctx, double *avg_bracket_ms, double *empty_bracket_ms, int32_t *launches);
 
+/* Same-box ceiling for the number above: a plain streaming read (16 B per lane, grid-stride, no reuse,
+ * non-temporal) of `bytes` bytes at `dev_buf` (device memory, 16-byte aligned, bytes a multiple of 16 and
+ * >= 4096; only read), timed the same way (HIP-event bracket per launch minus the empty-kernel bracket,
+ * averaged over `launches` (1..1000) launches) for grids of 1, 2, 4, 8 and 16 workgroups per compute
+ * unit; reports the best shape's GB/s and, optionally, its microseconds per launch.  Uses the score
+ * scratch of the workspace as its sink; synchronises `stream`; must not be called between
+ * fc_profile_begin and fc_profile_end (FC_ERR_STATE). */
+int fc_measure_stream_read(fc_ctx *ctx, const void *dev_buf, uint64_t bytes, int32_t launches, void *stream,
+                           double *gbps, double *us_per_launch);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,7 +31,7 @@ class fc_stability_args(C.Structure):
 EXPORTS = ["fc_workspace_bytes", "fc_host_scratch_bytes", "fc_create", "fc_destroy", "fc_status_string",
            "fc_last_error", "fc_write_kv_pages", "fc_build_minmax", "fc_rerank_topk", "fc_promote_pages",
            "fc_sparse_decode_attn", "fc_append_kv", "fc_offload_pages", "fc_stability_profile", "fc_classify_heads",
-           "fc_check_device_state", "fc_profile_begin", "fc_profile_end"]
+           "fc_check_device_state", "fc_profile_begin", "fc_profile_end", "fc_measure_stream_read"]
 
 
 class fc_config(C.Structure):
@@ -102,6 +102,8 @@ def load() -> C.CDLL:
         L.fc_check_device_state.argtypes = [C.c_void_p, C.c_void_p]
         L.fc_profile_begin.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
         L.fc_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
+        L.fc_measure_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p,
+                                             C.POINTER(C.c_double), C.POINTER(C.c_double)]
         _lib = L
     return _lib
 
@@ -244,3 +246,10 @@ class Context:
         ms, empty, n = C.c_double(), C.c_double(), C.c_int32()
         self._check(self.lib.fc_profile_end(self.handle, C.byref(ms), C.byref(empty), C.byref(n)))
         return ms.value, empty.value, n.value
+
+    def fc_measure_stream_read(self, buf, nbytes: int, launches: int = 16, stream=None):
+        """(GB/s, microseconds per launch) of a plain streaming read of the first nbytes of `buf`."""
+        g, us = C.c_double(), C.c_double()
+        self._check(self.lib.fc_measure_stream_read(self.handle, _ptr(buf), nbytes, launches,
+                                                    self._stream(stream), C.byref(g), C.byref(us)))
+        return g.value, us.value

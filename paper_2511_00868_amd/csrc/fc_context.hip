@@ -260,3 +260,72 @@ extern "C" int fc_profile_end(fc_ctx *ctx, double *avg_bracket_ms, double *empty
     if (launches) *launches = ctx->prof_used;
     return FC_OK;
 }
+
+// Plain streaming read used as the same-box ceiling for the attention kernel: 16 B per lane, grid-stride,
+// eight loads in flight per lane, every byte read once and folded into one word per workgroup.
+typedef unsigned int fc_u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void fc_stream_read_kernel(const fc_u32x4 *__restrict__ p, uint64_t n16,
+                                                             uint32_t *__restrict__ sink, uint32_t sink_n)
+{
+    uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    uint32_t acc = 0;
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        fc_u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    for (; i < n16; i += stride) {
+        fc_u32x4 v = __builtin_nontemporal_load(p + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) acc ^= __shfl_xor(acc, o);
+    if ((threadIdx.x & 63) == 0) sink[blockIdx.x % sink_n] = acc;
+}
+
+extern "C" int fc_measure_stream_read(fc_ctx *ctx, const void *dev_buf, uint64_t bytes, int32_t launches,
+                                      void *stream, double *gbps, double *us_per_launch)
+{
+    if (!ctx || !dev_buf || !gbps) return FC_ERR_INVALID_ARG;
+    FC_REQUIRE(ctx, bytes >= 4096 && bytes % 16 == 0 && ((uintptr_t)dev_buf & 15) == 0,
+               "fc_measure_stream_read: buffer must be 16-byte aligned, at least 4 KiB, a multiple of 16 bytes");
+    FC_REQUIRE(ctx, launches >= 1 && launches <= 1000, "fc_measure_stream_read: launches out of range");
+    if (ctx->profiling) return fc_fail(ctx, FC_ERR_STATE, "fc_measure_stream_read: fc_profile_begin is active");
+    hipStream_t s = (hipStream_t)stream;
+    int st = fc_profile_begin(ctx, 1, s);   // creates the events, measures the empty-kernel bracket
+    ctx->profiling = false;
+    if (st != FC_OK) return st;
+    // sink: the score scratch, which every rerank overwrites anyway (at least one float per page of one head)
+    uint32_t *sink = (uint32_t *)(ctx->ws + ctx->lay.scores);
+    const size_t score_words = (ctx->lay.seg_start - ctx->lay.scores) / 4;
+    const uint32_t sink_n = (uint32_t)(score_words > 65536 ? 65536 : score_words);
+    if (sink_n < 1) return fc_fail(ctx, FC_ERR_WORKSPACE, "fc_measure_stream_read: no scratch word available");
+    double best_ms = 0.0;
+    for (int per_cu = 1; per_cu <= 16; per_cu *= 2) {
+        const int grid = ctx->num_cus * per_cu;
+        for (int i = 0; i < launches + 2; ++i) {
+            FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * i], s));
+            hipLaunchKernelGGL(fc_stream_read_kernel, dim3(grid), dim3(256), 0, s, (const fc_u32x4 *)dev_buf,
+                               bytes / 16, sink, sink_n);
+            FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * i + 1], s));
+        }
+        FC_HIP(ctx, hipGetLastError());
+        FC_HIP(ctx, hipStreamSynchronize(s));
+        double tot = 0.0;
+        for (int i = 2; i < launches + 2; ++i) {
+            float ms = 0.f;
+            FC_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+            tot += ms;
+        }
+        double ms = tot / launches - ctx->prof_empty_ms;
+        if (ms > 0.0 && (best_ms == 0.0 || ms < best_ms)) best_ms = ms;
+    }
+    if (!(best_ms > 0.0)) return fc_fail(ctx, FC_ERR_STATE, "fc_measure_stream_read: no positive duration measured");
+    *gbps = (double)bytes / (best_ms * 1e-3) / 1e9;
+    if (us_per_launch) *us_per_launch = best_ms * 1e3;
+    return FC_OK;
+}

@@ -160,3 +160,30 @@ def test_per_sequence_rerank_phases():
                 assert (np.abs(got[b] - ref).max(axis=1) / np.abs(ref).max(axis=1)).max() <= 2e-3
     finally:
         s.close()
+
+
+def test_stream_read_measurement_reads_in_bounds_and_rejects_bad_arguments():
+    """The same-box ceiling of the benchmark: a plain read of a buffer.  Odd sizes exercise the ragged tail of
+    the grid-stride loop; guard words after the buffer stay untouched (the kernel only reads the buffer, its
+    sink is the workspace)."""
+    import torch
+    ctx = binding.Context(num_q_heads=8, num_kv_heads=2, max_batch=2, max_pages_per_seq=16, max_topk=4)
+    try:
+        buf = torch.arange(0, (8 << 20) // 4 + 64, dtype=torch.int32, device="cuda")
+        before = buf.clone()
+        for nbytes in (4096, 4096 + 16, (1 << 20) + 48, 8 << 20):
+            gbs, us = ctx.fc_measure_stream_read(buf, nbytes, 4)
+            assert gbs > 0 and us > 0
+        assert torch.equal(buf, before)
+        for bad in (dict(nbytes=100), dict(nbytes=4096 + 8), dict(launches=0), dict(launches=5000)):
+            kw = {"nbytes": 4096, "launches": 2, **bad}
+            with pytest.raises(binding.FlexiCacheError) as e:
+                ctx.fc_measure_stream_read(buf, kw["nbytes"], kw["launches"])
+            assert e.value.status == binding.FC_ERR_INVALID_ARG
+        ctx.fc_profile_begin(1)
+        with pytest.raises(binding.FlexiCacheError) as e:
+            ctx.fc_measure_stream_read(buf, 4096, 2)
+        assert e.value.status == binding.FC_ERR_STATE
+        ctx.fc_profile_end()
+    finally:
+        ctx.close()
