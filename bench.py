@@ -20,8 +20,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per whole-pass attention launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the same
-# counter reads for a copy kernel of known size (fc_write_pages_kernel in the same run)
-MEASURED_TRAFFIC_BYTES = {"cfg2_llama8b_32k": 584.96e6}
+# counter reads for a kernel of known size in the same run (reads: fc_stream_read_kernel, factor 1.9999;
+# writes: fc_write_pages_kernel, factor 1.000)
+MEASURED_TRAFFIC_BYTES = {"cfg2_llama8b_32k": 593.62e6}
 
 
 def attention_bytes(cfg, unstable_topk: bool = False) -> int:
