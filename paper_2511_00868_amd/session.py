@@ -52,7 +52,7 @@ def list_capacity(cfg: DecodeConfig) -> int:
     """Kmax: entries of a page list / free list: the budget plus the pages appended tokens can start
     between two reranks (they join the resident list at once and leave it at the next rerank)."""
     cur = max(cfg.num_pages(b) for b in range(cfg.batch))
-    return min(cfg.max_topk, cur) + cfg.growth_pages + (1 if cfg.append_tokens else 0)
+    return min(min(cfg.max_topk, cur) + cfg.growth_pages + (1 if cfg.append_tokens else 0), cfg.max_pages)
 
 
 def pool_blocks_needed(cfg: DecodeConfig) -> int:

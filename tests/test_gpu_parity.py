@@ -208,3 +208,30 @@ def test_other_ways_of_running_a_rerank_step(overlap):
     not splitting at all must give the same results."""
     _run(synth.make_config(5, batch=3, ctx=8192, steps=9), overlap=overlap)
     _run(synth.make_config(2, batch=2, ctx=4096 + 7, steps=5), overlap=overlap)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_small_configurations(seed):
+    """Shapes nobody chose by hand: batch, head counts, group size, ragged contexts, budgets (some above the
+    page count), rerank interval, stable flags, block order, dynamics, growth, wavefront count, promotion
+    mode, the way a rerank step is overlapped and the treatment of unstable heads drawn from a seed; the
+    whole loop is checked against the oracle like the named configurations."""
+    rng = np.random.default_rng(1000 + seed)
+    batch = int(rng.integers(1, 6))
+    Hkv = int(rng.choice([1, 2, 3, 5, 8, 12]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    ctx = tuple(int(x) for x in rng.integers(1, 2500, size=batch))
+    topk = tuple(int(max(1, rng.integers(1, 2 + (-(-c // 16)) * 5 // 4))) for c in ctx)
+    stable = tuple(bool(x) for x in rng.integers(0, 2, size=Hkv))
+    dynamics = str(rng.choice(["static", "unstable_resample", "drift"]))
+    grow = int(rng.choice([0, 0, 7, 40]))
+    steps = 7
+    cfg = synth.DecodeConfig(name=f"random_{seed}", index=1, batch=batch, num_q_heads=Hkv * G, num_kv_heads=Hkv,
+                             ctx=ctx, stable=stable, topk=topk, steps=steps, rerank_interval=int(rng.integers(1, 5)),
+                             hot_per_head=int(rng.integers(1, 4)), dynamics="static" if grow else dynamics,
+                             dynamics_pages=1, shuffle_blocks=bool(rng.integers(0, 2)), append_tokens=grow,
+                             seed=int(rng.integers(1, 1 << 30)))
+    print(cfg, flush=True)
+    _run(cfg, attn_waves=int(rng.choice([0, 4, 16, 64])),
+         promote_mode=int(rng.choice([binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_MEMCPY])),
+         overlap=[True, "heads", False][int(rng.integers(0, 3))], unstable_topk=bool(rng.integers(0, 4) == 0))
