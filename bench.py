@@ -99,14 +99,14 @@ def main():
     ap.add_argument("--promote-mode", choices=["gather", "memcpy"], default="gather")
     ap.add_argument("--attn-waves", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--kernel-event-stride", type=int, default=4, help="bracket every n-th whole-pass attention launch with HIP events")
+    ap.add_argument("--kernel-event-stride", type=int, default=8, help="bracket every n-th whole-pass attention launch with HIP events")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not bracket the attention kernel with HIP events")
     ap.add_argument("--paper-unstable-topk", action="store_true",
                     help="the paper's own treatment of unstable heads: rescored every step, top-K attention")
     ap.add_argument("--append", action="store_true",
                     help="grow every context by one token per step (fc_append_kv: page write, MinMax update, offload on fill)")
     ap.add_argument("--no-overlap", action="store_true", help="run rerank, promotion and attention back to back on one stream")
-    ap.add_argument("--overlap-by", choices=["pages", "heads"], default="pages",
+    ap.add_argument("--overlap-by", choices=["pages", "heads", "inline", "heads-inline"], default="inline",
                     help="how a rerank step's attention is split around the page copies")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
@@ -138,7 +138,7 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
-    sess.overlap = False if args.no_overlap else ("heads" if args.overlap_by == "heads" else True)
+    sess.overlap = False if args.no_overlap else (True if args.overlap_by == "pages" else args.overlap_by)
     main = torch.cuda.current_stream()
 
     def run_step(t, marks=None):
@@ -205,6 +205,7 @@ def main():
     ceil_bytes = min(pool_bytes, attention_bytes(cfg, args.paper_unstable_topk)) // 4096 * 4096
     ceil_gbs, ceil_us = sess.ctx.fc_measure_stream_read(sess.kv_pool, ceil_bytes, 16, main)
 
+    inline = sess.overlap in ("inline", "heads-inline")
     n_rerank = sum(is_rer_timed)
     a_bytes, r_bytes = attention_bytes(cfg, args.paper_unstable_topk), rerank_bytes(cfg)
     step_bytes = a_bytes * args.steps + r_bytes * n_rerank
@@ -234,11 +235,15 @@ def main():
         "attn_call_GBps_plain_step": round(a_bytes / (float(np.median(plain_us)) * 1e-6) / 1e9, 1) if plain_us else None,
         "rerank_topk_us_per_invocation": round(float(np.median(rr_us)), 2) if rr_us else None,
         "rerank_topk_us_per_step_amortised": round(float(np.median(rr_us)) / cfg.rerank_interval, 2) if rr_us else None,
-        "recycle_us_per_invocation": round(float(np.median(pr_us)), 2) if pr_us else None,
-        "page_copies_us_per_invocation": round(float(np.median(cp_us)), 2) if cp_us else None,
+        # with the copies in line the recycling kernel and the copies are one enqueue on one stream: only their sum is seen
+        "recycle_us_per_invocation": round(float(np.median(pr_us)), 2) if pr_us and not inline else None,
+        "page_copies_us_per_invocation": round(float(np.median(cp_us)), 2) if cp_us and not inline else None,
+        "recycle_and_page_copies_us_per_invocation": round(float(np.median(np.add(pr_us, cp_us))), 2) if pr_us else None,
         "rerank_invocations": n_rerank, "promoted_pages_last_rerank": promoted_last,
         "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
-        "rerank_step_overlap": "none" if not sess.overlap else ("by head class" if sess.overlap == "heads" else "by page (resident, then promoted)"),
+        "rerank_step_overlap": {False: "none", True: "by page (resident, then promoted)", "heads": "by head class",
+                                "inline": "by page, copies in line on the main stream, resident pages on the other stream",
+                                "heads-inline": "by head class, copies in line on the main stream, unstable heads on the other stream"}[sess.overlap],
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None and not args.paper_unstable_topk and not args.append else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,

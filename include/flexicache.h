@@ -148,7 +148,11 @@ int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *args, void *stream);
  *   of block_table become 0, promoted entries get their block, resident_* becomes new_*.
  *   Each promoted page is then copied host_pool[host_block_table[..]] -> kv_pool[block] on
  *   `side_stream`, ordered after the bookkeeping kernel on `main_stream`; the next
- *   fc_sparse_decode_attn on this context waits (on the GPU) for those copies.
+ *   fc_sparse_decode_attn on this context that reads stable heads' pages waits (on the GPU) for those
+ *   copies, whatever stream it runs on.  side_stream may be the same stream as main_stream: the
+ *   copies then follow the bookkeeping kernel in line, with no event between them, which is the
+ *   shortest path to the promoted pages; work that should hide the copies then goes to another
+ *   stream (see head_subset of fc_sparse_decode_attn).
  * mode FC_PROMOTE_GATHER: one kernel on side_stream reads pinned host memory directly; the host
  *   never waits.  mode FC_PROMOTE_MEMCPY: the host waits for the copy list, then issues one
  *   hipMemcpyAsync per page on side_stream. */
@@ -193,7 +197,12 @@ int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream
  *   by head   FC_HEADS_UNSTABLE attends over the unstable heads only (no wait); FC_HEADS_STABLE waits for
  *             the copies, attends over the stable heads and writes the output rows of both classes (of
  *             the stable heads only, if no FC_HEADS_UNSTABLE call preceded it on this context).
- * The output rows are complete only after the second call of a pair.  FC_HEADS_ALL: everything in one pass. */
+ * The output rows are complete only after the second call of a pair.  FC_HEADS_ALL: everything in one pass.
+ * The two calls of a pair may be given different streams: the library orders the first call after the
+ * last fc_promote_pages bookkeeping kernel (whose tables and flags it reads) and the merge of the
+ * second call after the first call.  Any other ordering between different streams is the caller's:
+ * in particular a call on another stream than the previous attention call's must not start before
+ * that call has finished (both use the context's workspace). */
 enum { FC_HEADS_ALL = 0, FC_HEADS_UNSTABLE = 1, FC_HEADS_STABLE = 2, FC_PAGES_RESIDENT = 3, FC_PAGES_PROMOTED = 4 };
 typedef struct {
     const void *q;               /* dev bf16 [batch][num_q_heads][D] */

@@ -474,11 +474,16 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
         merge_mask = all;
     }
     if (sub == FC_HEADS_STABLE && ctx->pending_pair == FC_HEADS_UNSTABLE) merge_mask = all;
+    // the two calls of a pair may sit on different streams: the merge then waits for the first call's stream
+    const bool wait_first = merge_now && merge_mask == all && ctx->pending_pair != 0 && ctx->first_stream != stream;
     ctx->pending_pair = first_of_pair ? sub : 0;
+    // block tables and promoted flags come from the last recycling kernel: a call on another stream than
+    // that kernel's is ordered after it here (on its own stream the order is already given)
+    if (ctx->diff_valid && stream != ctx->diff_stream) FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_diff_done, 0));
     const bool needs_copies = sub != FC_HEADS_UNSTABLE && sub != FC_PAGES_RESIDENT && (p.active_mask & mask);
-    if (ctx->copies_pending && needs_copies) {   // promoted pages still in flight on the side stream
-        FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_copies_done, 0));
-        ctx->copies_pending = false;
+    if (needs_copies) {   // promoted pages may still be in flight
+        const int st = fc_wait_for_copies(ctx, stream);
+        if (st != FC_OK) return st;
     }
     if (p.active_mask != 0) {
         // kernel timing covers whole passes only: the split launches move other byte counts
@@ -496,6 +501,11 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
             ++ctx->prof_used;
         }
     }
+    if (first_of_pair) {
+        FC_HIP(ctx, hipEventRecord(ctx->ev_first_done, s));
+        ctx->first_stream = stream;
+    }
+    if (wait_first) FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_first_done, 0));
     if (merge_now && merge_mask != 0) {
         p.active_mask = merge_mask;
         hipLaunchKernelGGL(fc_attn_merge_kernel, dim3(p.batch * p.Hkv, p.G), dim3(256), 0, s, p);

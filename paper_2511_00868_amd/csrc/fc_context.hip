@@ -140,7 +140,10 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
     fc_make_layout(c->cfg, c->attn_waves, &c->lay);
     if (c->lay.total > workspace_bytes) { delete c; return FC_ERR_WORKSPACE; }
     if (hipEventCreateWithFlags(&c->ev_diff_done, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_copies_done, hipEventDisableTiming) != hipSuccess) {
+        hipEventCreateWithFlags(&c->ev_copies_done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_first_done, hipEventDisableTiming) != hipSuccess) {
+        if (c->ev_diff_done) (void)hipEventDestroy(c->ev_diff_done);
+        if (c->ev_copies_done) (void)hipEventDestroy(c->ev_copies_done);
         delete c;
         return FC_ERR_HIP;
     }
@@ -149,10 +152,12 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
         hipDeviceSynchronize() != hipSuccess) {
         (void)hipEventDestroy(c->ev_diff_done);
         (void)hipEventDestroy(c->ev_copies_done);
+        (void)hipEventDestroy(c->ev_first_done);
         delete c;
         return FC_ERR_HIP;
     }
     c->copies_pending = false;
+    c->diff_valid = false;
     c->pending_pair = 0;
     c->promote_calls = 0;
     c->gather_blocks = 32;
@@ -175,6 +180,7 @@ extern "C" int fc_destroy(fc_ctx *ctx)
     if (!ctx) return FC_ERR_INVALID_ARG;
     (void)hipEventDestroy(ctx->ev_diff_done);
     (void)hipEventDestroy(ctx->ev_copies_done);
+    (void)hipEventDestroy(ctx->ev_first_done);
     for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
         if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
     delete ctx;

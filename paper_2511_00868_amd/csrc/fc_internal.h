@@ -48,6 +48,12 @@ struct fc_ctx {
     fc_ws_layout lay;
     hipEvent_t ev_diff_done;
     hipEvent_t ev_copies_done;
+    hipEvent_t ev_first_done;   // the first attention call of a pair has been enqueued up to here
+    void *diff_stream;          // stream of the last block-recycling kernel (ev_diff_done), if diff_valid
+    bool diff_valid;
+    void *first_stream;         // stream of the pending first call of a pair
+    void *copies_stream;        // stream the pending page copies were enqueued on
+    bool copies_recorded;       // ev_copies_done has been recorded behind them (not done for in-line copies until another stream asks)
     bool copies_pending;
     int pending_pair;        // FC_HEADS_UNSTABLE or FC_PAGES_RESIDENT has left partials for its partner call to merge, else 0
     unsigned promote_calls;
@@ -63,6 +69,7 @@ struct fc_ctx {
 };
 
 int fc_fail(fc_ctx *ctx, int status, const char *fmt, ...);
+int fc_wait_for_copies(fc_ctx *ctx, void *stream);
 int fc_hip_fail(fc_ctx *ctx, hipError_t e, const char *what);
 uint64_t fc_stable_mask(const fc_config &cfg, const uint8_t *stable_flag);
 

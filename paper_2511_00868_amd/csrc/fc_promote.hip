@@ -243,6 +243,21 @@ __global__ __launch_bounds__(256) void fc_gather_pages_kernel(const int32_t *__r
     }
 }
 
+// Orders `stream` after the page copies of the last fc_promote_pages, if they may still be running.
+int fc_wait_for_copies(fc_ctx *ctx, void *stream)
+{
+    if (!ctx->copies_pending) return FC_OK;
+    if (ctx->copies_stream != stream) {
+        if (!ctx->copies_recorded) {
+            FC_HIP(ctx, hipEventRecord(ctx->ev_copies_done, (hipStream_t)ctx->copies_stream));
+            ctx->copies_recorded = true;
+        }
+        FC_HIP(ctx, hipStreamWaitEvent((hipStream_t)stream, ctx->ev_copies_done, 0));
+    }
+    ctx->copies_pending = false;
+    return FC_OK;
+}
+
 extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *main_stream, void *side_stream)
 {
     if (!ctx) return FC_ERR_INVALID_ARG;
@@ -253,7 +268,6 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     FC_REQUIRE(ctx, a->batch >= 1 && a->batch <= ctx->cfg.max_batch, "fc_promote_pages: batch=%d outside 1..%d", a->batch, ctx->cfg.max_batch);
     FC_REQUIRE(ctx, a->num_pool_blocks >= 2 && a->num_host_blocks >= 1, "fc_promote_pages: pool sizes must be positive");
     FC_REQUIRE(ctx, a->mode == FC_PROMOTE_GATHER || a->mode == FC_PROMOTE_MEMCPY, "fc_promote_pages: unknown mode %d", a->mode);
-    FC_REQUIRE(ctx, main_stream != side_stream, "fc_promote_pages: main and side stream must differ");
 
     fc_promote_params p;
     p.new_pages = a->new_pages;
@@ -294,8 +308,8 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     if (ctx->copies_pending) {
         // copies of an earlier call may still be running on the side stream: this call's bookkeeping
         // must not hand their destination blocks out again before they have landed
-        FC_HIP(ctx, hipStreamWaitEvent(ms, ctx->ev_copies_done, 0));
-        ctx->copies_pending = false;
+        const int st = fc_wait_for_copies(ctx, main_stream);
+        if (st != FC_OK) return st;
     }
     const size_t list_bytes = 2 * (size_t)p.Kmax * sizeof(int32_t);
     p.lds_lists = list_bytes <= 48 * 1024;
@@ -303,9 +317,11 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     ++ctx->promote_calls;
     FC_HIP(ctx, hipGetLastError());
     FC_HIP(ctx, hipEventRecord(ctx->ev_diff_done, ms));
+    ctx->diff_stream = main_stream;
+    ctx->diff_valid = true;
 
     if (a->mode == FC_PROMOTE_GATHER) {
-        FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
+        if (ss != ms) FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
         hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, ss, p.copy_list, p.counters + 2 + p.parity,
                            p.list_capacity, (const uint4 *)a->host_pool, (uint4 *)a->kv_pool);
         FC_HIP(ctx, hipGetLastError());
@@ -321,7 +337,11 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
             FC_HIP(ctx, hipMemcpyAsync(kp + dst * FC_PAGE_BYTES, hp + src * FC_PAGE_BYTES, FC_PAGE_BYTES, hipMemcpyHostToDevice, ss));
         }
     }
-    FC_HIP(ctx, hipEventRecord(ctx->ev_copies_done, ss));
+    // in-line copies are followed by the caller's next work on the same stream anyway; an event behind them
+    // would only hold that work up (a few microseconds per record), so it is recorded when another stream asks
+    ctx->copies_recorded = ss != ms;
+    if (ctx->copies_recorded) FC_HIP(ctx, hipEventRecord(ctx->ev_copies_done, ss));
     ctx->copies_pending = true;
+    ctx->copies_stream = side_stream;
     return FC_OK;
 }

@@ -108,7 +108,7 @@ class DecodeSession:
         self.lse = torch.zeros((B, cfg.num_q_heads), dtype=torch.float32, device=self.dev)
         self.main = torch.cuda.current_stream(self.dev)
         self.copy = torch.cuda.Stream(self.dev)            # host -> HBM page copies (default priority)
-        self.overlap = True
+        self.overlap = "inline"
         self.events = None     # optional dict of torch events a benchmark wants recorded on a rerank step
         self.stable = list(cfg.stable)
         for b in range(B):
@@ -214,23 +214,28 @@ class DecodeSession:
                                   promoted_count=self.promoted_count, promoted_flags=self.promoted_flags,
                                   total_promoted=self.total_promoted)
 
-    def attend(self, head_subset: int = binding.FC_HEADS_ALL):
+    def attend(self, head_subset: int = binding.FC_HEADS_ALL, stream=None):
         listed = [True] * len(self.stable) if self.unstable_topk else self.stable
         self.ctx.fc_sparse_decode_attn(q=self.q, kv_pool=self.kv_pool, num_pool_blocks=self.num_pool_blocks,
                                        block_table=self.block_table, context_lens=self.context_lens,
                                        stable_flag=listed, topk_pages=self.resident_pages,
                                        topk_count=self.resident_count, batch=self.cfg.batch, out=self.out,
                                        lse=self.lse, head_subset=head_subset, promoted_flags=self.promoted_flags,
-                                       stream=self.main)
+                                       stream=stream or self.main)
 
     def step(self, t: int):
         """One pass of the hot path for decode step t (queries already set on the main stream).
 
-        On a rerank step scoring, selection and block recycling run first; the page copies then go
-        to the copy stream while the main stream attends over everything that is already in HBM
-        (all pages of unstable heads, the kept pages of stable heads); the promoted pages follow once
-        the copies have landed (the library makes that call wait, on the GPU, for the copies).
-        `overlap = "heads"` splits by head class instead, `overlap = False` does not split."""
+        On a rerank step scoring, selection and block recycling run first.  `overlap = "inline"` (default)
+        keeps the whole dependent chain (recycling, page copies, attention over the promoted pages, merge)
+        on the main stream with no event between its links, and gives the work that hides the copies
+        (attention over everything already in HBM: all pages of unstable heads, the kept pages of stable
+        heads) to the second stream.  `overlap = True` puts the copies on the second stream instead and
+        keeps both attention calls on the main stream (the second waits, on the GPU, for the copies);
+        "heads" / "heads-inline" split by head class instead of by page (with "heads-inline" the unstable
+        heads start before the rerank); `overlap = False` does not split."""
+        inline = self.overlap in ("inline", "heads-inline")
+        copy = self.main if inline else self.copy
         if self.unstable_topk:
             if not all(self.stable):
                 self.rerank_unstable()
@@ -241,23 +246,35 @@ class DecodeSession:
                 self.rerank()
                 if ev is not None:
                     ev["rerank_end"].record(self.main)
-                self.promote()
+                self.promote(copy_stream=copy)
                 if ev is not None:
                     ev["recycle_end"].record(self.main)
-                    ev["copies_end"].record(self.copy)
+                    ev["copies_end"].record(copy)
             self.attend()
             return
         if self.cfg.is_rerank_step(t) and any(self.stable):
             ev = self.events
+            heads_first = self.overlap == "heads-inline" and not all(self.stable)
+            if heads_first:
+                # nothing the unstable heads read is touched by the rerank: start them at once, beside it
+                self.copy.wait_stream(self.main)
+                self.attend(binding.FC_HEADS_UNSTABLE, stream=self.copy)
             if ev is not None:
                 ev["rerank_begin"].record(self.main)
             self.rerank()
             if ev is not None:
                 ev["rerank_end"].record(self.main)
-            self.promote()
+            self.promote(copy_stream=copy)
             if ev is not None:
                 ev["recycle_end"].record(self.main)
-                ev["copies_end"].record(self.copy)
+                ev["copies_end"].record(copy)
+            if heads_first:
+                self.attend(binding.FC_HEADS_STABLE)
+                return
+            if inline:
+                self.attend(binding.FC_PAGES_RESIDENT, stream=self.copy)
+                self.attend(binding.FC_PAGES_PROMOTED)
+                return
             if self.overlap == "heads" and not all(self.stable):
                 self.attend(binding.FC_HEADS_UNSTABLE)
                 self.attend(binding.FC_HEADS_STABLE)

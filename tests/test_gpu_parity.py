@@ -202,10 +202,11 @@ def test_one_very_long_sequence_many_partials_per_item():
     _run(cfg)
 
 
-@pytest.mark.parametrize("overlap", ["heads", False])
+@pytest.mark.parametrize("overlap", [True, "heads", False, "heads-inline"])
 def test_other_ways_of_running_a_rerank_step(overlap):
-    """The default splits a rerank step by page (resident, then promoted); splitting by head class and
-    not splitting at all must give the same results."""
+    """The default splits a rerank step by page with the copies in line on the main stream and the resident
+    pages on the second stream; copies on the second stream, splitting by head class (either way) and not
+    splitting at all must give the same results."""
     _run(synth.make_config(5, batch=3, ctx=8192, steps=9), overlap=overlap)
     _run(synth.make_config(2, batch=2, ctx=4096 + 7, steps=5), overlap=overlap)
 
@@ -234,4 +235,4 @@ def test_random_small_configurations(seed):
     print(cfg, flush=True)
     _run(cfg, attn_waves=int(rng.choice([0, 4, 16, 64])),
          promote_mode=int(rng.choice([binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_MEMCPY])),
-         overlap=[True, "heads", False][int(rng.integers(0, 3))], unstable_topk=bool(rng.integers(0, 4) == 0))
+         overlap=[True, "heads", False, "inline", "heads-inline"][int(rng.integers(0, 5))], unstable_topk=bool(rng.integers(0, 4) == 0))

@@ -34,11 +34,11 @@ def test_bad_arguments_are_rejected_before_anything_is_launched():
                                topk_pages=tbl, topk_count=lens)
         assert e.value.status == binding.FC_ERR_INVALID_ARG
         s = torch.cuda.current_stream()
-        with pytest.raises(binding.FlexiCacheError) as e:   # main and side stream must differ
+        with pytest.raises(binding.FlexiCacheError) as e:
             ctx.fc_promote_pages(new_pages=tbl, new_count=lens, resident_pages=tbl, resident_count=lens, block_table=tbl,
                                  host_block_table=tbl, free_blocks=tbl, free_count=lens, stable_flag=[True, False],
                                  kv_pool=pool, num_pool_blocks=4, host_pool=pool, num_host_blocks=4, batch=2,
-                                 main_stream=s, side_stream=s)
+                                 main_stream=s, side_stream=s, mode=7)
         assert e.value.status == binding.FC_ERR_INVALID_ARG
         with pytest.raises(binding.FlexiCacheError):
             ctx.fc_write_kv_pages(q, q, 17, tbl, pool, 4)                          # more pages than max_pages_per_seq
@@ -95,15 +95,19 @@ def _run_steps_against_oracle(s, wl, cfg, steps, before_step=None):
             assert err.max() <= 2e-3
 
 
-@pytest.mark.parametrize("mode", [binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_MEMCPY])
-def test_attention_waits_for_delayed_copies_into_poisoned_blocks(mode):
-    """Every block a promoted page will land in holds NaN until its copy arrives, and the copy stream is
+@pytest.mark.parametrize("mode,overlap", [(binding.FC_PROMOTE_GATHER, True), (binding.FC_PROMOTE_MEMCPY, True),
+                                          (binding.FC_PROMOTE_GATHER, "heads"), (binding.FC_PROMOTE_GATHER, "inline"),
+                                          (binding.FC_PROMOTE_GATHER, "heads-inline"), (binding.FC_PROMOTE_MEMCPY, "inline")])
+def test_attention_waits_for_delayed_copies_into_poisoned_blocks(mode, overlap):
+    """Every block a promoted page will land in holds NaN until its copy arrives, and the second stream is
     held back by a long sleep kernel before each rerank step: the stable heads' attention must still see
-    the copied pages (a premature read would surface as NaN)."""
+    the copied pages (a premature read would surface as NaN).  In the in-line modes the second stream
+    carries the first attention call of the pair instead of the copies: the merge must wait for it."""
     import torch
     cfg = synth.make_config(5, batch=2, ctx=4096, steps=9)
     wl = synth.Workload(cfg)
     s = DecodeSession(cfg, wl, promote_mode=mode)
+    s.overlap = overlap
     try:
         fb, fc = s.free_blocks.cpu().numpy(), s.free_count.cpu().numpy()
         ids = [int(x) for b in range(cfg.batch) for h in range(cfg.num_kv_heads) for x in fb[b, h, :fc[b, h]]]
