@@ -106,7 +106,7 @@ def main():
     ap.add_argument("--append", action="store_true",
                     help="grow every context by one token per step (fc_append_kv: page write, MinMax update, offload on fill)")
     ap.add_argument("--no-overlap", action="store_true", help="run rerank, promotion and attention back to back on one stream")
-    ap.add_argument("--overlap-by", choices=["pages", "heads", "inline", "heads-inline"], default="inline",
+    ap.add_argument("--overlap-by", choices=["auto", "pages", "heads", "inline", "heads-inline"], default="auto",
                     help="how a rerank step's attention is split around the page copies")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
@@ -138,7 +138,10 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
-    sess.overlap = False if args.no_overlap else (True if args.overlap_by == "pages" else args.overlap_by)
+    if args.no_overlap:
+        sess.overlap = False
+    elif args.overlap_by != "auto":      # auto: the session's own choice (in line for all but tiny workloads)
+        sess.overlap = True if args.overlap_by == "pages" else args.overlap_by
     main = torch.cuda.current_stream()
 
     def run_step(t, marks=None):

@@ -309,7 +309,8 @@ int fc_profile_end(fc_ctx *ctx, double *avg_bracket_ms, double *empty_bracket_ms
  * non-temporal) of `bytes` bytes at `dev_buf` (device memory, 16-byte aligned, bytes a multiple of 16 and
  * >= 4096; only read), timed the same way (HIP-event bracket per launch minus the empty-kernel bracket,
  * averaged over `launches` (1..1000) launches) for grids of 1, 2, 4, 8 and 16 workgroups per compute
- * unit; reports the best shape's GB/s and, optionally, its microseconds per launch.  Uses the score
+ * unit; reports the best shape's GB/s and, optionally, its microseconds per launch (for a read so short
+ * that it does not stand out from the bracket's own latency, the uncorrected bracket time is used).  Uses the score
  * scratch of the workspace as its sink; synchronises `stream`; must not be called between
  * fc_profile_begin and fc_profile_end (FC_ERR_STATE). */
 int fc_measure_stream_read(fc_ctx *ctx, const void *dev_buf, uint64_t bytes, int32_t launches, void *stream,

@@ -327,7 +327,9 @@ extern "C" int fc_measure_stream_read(fc_ctx *ctx, const void *dev_buf, uint64_t
             FC_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
             tot += ms;
         }
-        double ms = tot / launches - ctx->prof_empty_ms;
+        const double raw = tot / launches;
+        // a read too short to stand out from the bracket's own latency: keep the raw bracket time (an upper bound)
+        const double ms = raw - ctx->prof_empty_ms > 0.05 * raw ? raw - ctx->prof_empty_ms : raw;
         if (ms > 0.0 && (best_ms == 0.0 || ms < best_ms)) best_ms = ms;
     }
     if (!(best_ms > 0.0)) return fc_fail(ctx, FC_ERR_STATE, "fc_measure_stream_read: no positive duration measured");

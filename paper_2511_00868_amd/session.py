@@ -108,7 +108,9 @@ class DecodeSession:
         self.lse = torch.zeros((B, cfg.num_q_heads), dtype=torch.float32, device=self.dev)
         self.main = torch.cuda.current_stream(self.dev)
         self.copy = torch.cuda.Stream(self.dev)            # host -> HBM page copies (default priority)
-        self.overlap = "inline"
+        # how a rerank step is run (see step()); splitting only pays when the attention is long enough to
+        # hide something behind: below ~64 MB per pass the extra launches and the stream hand-overs cost more
+        self.overlap = "inline" if cfg.pages_attended() * 8192 >= (64 << 20) else False
         self.events = None     # optional dict of torch events a benchmark wants recorded on a rerank step
         self.stable = list(cfg.stable)
         for b in range(B):
@@ -235,7 +237,7 @@ class DecodeSession:
         "heads" / "heads-inline" split by head class instead of by page (with "heads-inline" the unstable
         heads start before the rerank); `overlap = False` does not split."""
         inline = self.overlap in ("inline", "heads-inline")
-        copy = self.main if inline else self.copy
+        copy = self.main if inline or not self.overlap else self.copy
         if self.unstable_topk:
             if not all(self.stable):
                 self.rerank_unstable()
