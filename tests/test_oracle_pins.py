@@ -427,3 +427,81 @@ def test_ties_at_the_budget_boundary_go_to_the_lower_page_index():
         got = oracle.select_topk(s, n * 16, K)
         ref = sorted(np.lexsort((np.arange(n), -s))[:min(K, n)])
         assert list(got) == ref
+
+
+# ---- pins found missing by mutating the oracle ---------------------------------------------------
+def test_selection_pads_its_output_with_minus_one():
+    import ctypes as C
+    s = np.array([3.0, 1.0, 2.0], dtype=np.float64)
+    out = np.full(6, 77, dtype=np.int32)
+    cnt = oracle.lib().fco_select_topk(s.ctypes.data_as(C.POINTER(C.c_double)), 3, 48, 16, 6,
+                                       out.ctypes.data_as(C.POINTER(C.c_int32)))
+    assert cnt == 3 and out.tolist() == [0, 1, 2, -1, -1, -1]
+    out[:] = 77
+    cnt = oracle.lib().fco_select_topk(s.ctypes.data_as(C.POINTER(C.c_double)), 3, 48, 16, 2,
+                                       out.ctypes.data_as(C.POINTER(C.c_int32)))
+    assert cnt == 2 and out.tolist() == [0, 2, 77, 77, 77, 77]     # writes K entries, no more
+
+
+def test_recycle_leaves_the_unused_blocks_in_order_as_the_new_free_list():
+    """Available blocks = the free list, then the evicted pages' blocks in ascending page order; promoted
+    pages take from the front; what is left, in that order, is the new free list (Sec. 3.4)."""
+    table = np.zeros(8, dtype=np.int32)
+    host = np.arange(50, 58, dtype=np.int32)
+    copies, free = oracle.recycle([], [2], table, host, [5, 3, 9, 4])
+    assert copies.tolist() == [[52, 5]] and free == [3, 9, 4] and table.tolist() == [0, 0, 5, 0, 0, 0, 0, 0]
+    copies, free = oracle.recycle([2], [2, 6, 7], table, host, free)           # nothing evicted, two promoted
+    assert copies.tolist() == [[56, 3], [57, 9]] and free == [4]
+    copies, free = oracle.recycle([2, 6, 7], [0], table, host, free)           # three evicted, one promoted
+    assert copies.tolist() == [[50, 4]] and free == [5, 3, 9]                   # blocks of pages 2, 6, 7
+    assert table.tolist() == [4, 0, 0, 0, 0, 0, 0, 0]
+    copies, free = oracle.recycle([0], [], table, host, free)                  # everything evicted
+    assert len(copies) == 0 and free == [5, 3, 9, 4] and not table.any()
+
+
+def test_whole_sequence_drivers_equal_the_per_head_routines_and_numpy():
+    rng = np.random.default_rng(77)
+    Hq, Hkv, D, ctx, P = 6, 3, 128, 75, 16
+    G, n, tpad = Hq // Hkv, 5, 80
+    q = rand_bf16(rng, (Hq, D))
+    k = rand_bf16(rng, (Hkv, tpad, D))
+    v = rand_bf16(rng, (Hkv, tpad, D))
+    mm = oracle.seq_build_minmax(k, ctx)
+    assert mm.shape == (Hkv, n, 2, D)
+    for h in range(Hkv):
+        kv = widen(k[h])
+        for p in range(n):
+            rows = kv[16 * p:min(16 * p + 16, ctx)]
+            np.testing.assert_array_equal(widen(mm[h, p, 0]), rows.min(0))
+            np.testing.assert_array_equal(widen(mm[h, p, 1]), rows.max(0))
+    stable = [True, False, True]
+    s = oracle.seq_scores(q, mm, stable)
+    qf, mf = widen(q), widen(mm)
+    for h in range(Hkv):
+        if not stable[h]:
+            assert np.all(np.isnan(s[h]))                       # untouched
+            continue
+        per_q = np.maximum(qf[h * G:(h + 1) * G, None, :] * mf[h, None, :, 0, :],
+                           qf[h * G:(h + 1) * G, None, :] * mf[h, None, :, 1, :]).sum(-1)
+        np.testing.assert_allclose(s[h], per_q.max(0), rtol=1e-13)
+    lists = [np.array([0, 2, 4]), np.arange(n), np.array([1])]
+    scale = 0.2
+    out, lse = oracle.seq_attention(q, k, v, ctx, lists, scale)
+    for hq in range(Hq):
+        h = hq // G
+        tok = np.concatenate([np.arange(16 * p, min(16 * p + 16, ctx)) for p in lists[h]])
+        z = scale * widen(k[h])[tok] @ widen(q[hq])
+        w = np.exp(z - z.max())
+        np.testing.assert_allclose(out[hq], (w / w.sum()) @ widen(v[h])[tok], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(lse[hq], z.max() + np.log(w.sum()), rtol=1e-13)
+
+
+def test_head_ranking_ties_go_to_the_lower_head_index_and_the_quota_is_a_floor():
+    ts = np.array([[0.5, 0.2, 0.2, 0.9, 0.2, 0.7, 0.8, 0.6]])          # three heads tie for the bottom quartile (2 of 8)
+    assert oracle.bottom_counts(ts).tolist() == [0, 1, 1, 0, 0, 0, 0, 0]
+    counts = np.array([3, 5, 5, 0, 5, 1, 2, 4], dtype=np.int32)
+    assert oracle.classify(counts).tolist() == [0, 1, 1, 0, 0, 0, 0, 0]       # 8 / 4 = 2 heads, ties to the lower index
+    assert oracle.classify(counts[:7]).tolist() == [0, 1, 0, 0, 0, 0, 0]      # floor(7 / 4) = 1
+    assert oracle.classify(counts, 3, 8).tolist() == [0, 1, 1, 0, 1, 0, 0, 0]  # floor(8 * 3 / 8) = 3
+    assert oracle.classify(np.arange(10, dtype=np.int32), 3, 10).sum() == 3    # floor(10 * 3 / 10) = 3, not (10 + 3) / 10
+    assert oracle.rco([0, 1, 2, 3], [0, 1, 2, 3], 4) == 0.0                     # K = N_t: chance level is 1, defined as 0
