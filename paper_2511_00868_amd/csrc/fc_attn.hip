@@ -375,6 +375,53 @@ __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
     const int n_parts = n_a + n_b;
     auto slot_of = [&](int i) -> size_t { return i < n_a ? slot_a + i : slot_b + (i - n_a); };
 
+    const int sub = tid >> 5, d4 = tid & 31;
+    if (n_parts <= 32) {
+        // The usual case (an item split over a few dozen wavefronts): every load is issued before any
+        // result is needed, so the kernel is two dependent memory round trips (schedule, partials) deep.
+        float4_t a4[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k = sub + 8 * i;
+            a4[i] = k < n_parts ? *reinterpret_cast<const float4_t *>(p.part_acc + (slot_of(k) * p.G + g) * FC_D + 4 * d4)
+                                : float4_t{0.f, 0.f, 0.f, 0.f};
+        }
+        float m = -INFINITY, l = 0.f;
+        if (tid < n_parts) {
+            const float *ml = p.part_ml + (slot_of(tid) * 16 + g) * 2;
+            m = ml[0];
+            l = ml[1];
+        }
+        float mstar = m;       // partials sit in the first wavefront's lanes 0..31
+#pragma unroll
+        for (int d = 16; d >= 1; d >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, d));
+        const float wt = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - mstar);
+        float lsum = wt * l;
+#pragma unroll
+        for (int d = 16; d >= 1; d >>= 1) lsum += __shfl_xor(lsum, d);
+        if (tid < 32) wts[tid] = wt;
+        if (tid == 0) {
+            red[0] = mstar;
+            red[1] = lsum;
+        }
+        __syncthreads();
+        float4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc += wts[sub + 8 * i] * a4[i];
+        accs[sub][d4] = acc;
+        __syncthreads();
+        mstar = red[0];
+        lsum = red[1];
+        if (tid < 32) {
+            float4_t r = accs[0][tid];
+#pragma unroll
+            for (int k = 1; k < 8; ++k) r += accs[k][tid];
+            *reinterpret_cast<float4_t *>(p.out + row * FC_D + 4 * tid) = r * (1.0f / lsum);
+        }
+        if (p.lse && tid == 0) p.lse[row] = (mstar + __builtin_amdgcn_logf(lsum)) * 0.6931471805599453f;
+        return;
+    }
+
     float mstar = -INFINITY;
     for (int i = tid; i < n_parts; i += 256) mstar = fmaxf(mstar, p.part_ml[(slot_of(i) * 16 + g) * 2]);
 #pragma unroll
@@ -384,7 +431,6 @@ __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
     mstar = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     __syncthreads();
 
-    const int sub = tid >> 5, d4 = tid & 31;
     float lsum = 0.f;
     float4_t acc = {0.f, 0.f, 0.f, 0.f};
     for (int base = 0; base < n_parts; base += 256) {
