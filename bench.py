@@ -236,6 +236,10 @@ def main():
         "rerank_exposed_us_per_step_amortised": round((float(np.median(rer_us)) - float(np.median(plain_us)))
                                                       / cfg.rerank_interval, 2) if rer_us and plain_us else None,
         "attn_call_GBps_plain_step": round(a_bytes / (float(np.median(plain_us)) * 1e-6) / 1e9, 1) if plain_us else None,
+        # attention and rerank alone, promotion (PCIe) left out: R attention calls and one fc_rerank_topk, from the medians
+        "attn_plus_rerank_GBps_excl_promotion": round((cfg.rerank_interval * a_bytes + r_bytes)
+                                                       / ((cfg.rerank_interval * float(np.median(plain_us)) + float(np.median(rr_us))) * 1e-6) / 1e9, 1)
+                                                 if plain_us and rr_us else None,
         "rerank_topk_us_per_invocation": round(float(np.median(rr_us)), 2) if rr_us else None,
         "rerank_topk_us_per_step_amortised": round(float(np.median(rr_us)) / cfg.rerank_interval, 2) if rr_us else None,
         # with the copies in line the recycling kernel and the copies are one enqueue on one stream: only their sum is seen
