@@ -15,7 +15,8 @@
  *     memory read during the call; "pinned" pointers are page-locked host memory that the GPU can
  *     address (hipHostMalloc / torch pin_memory).  The library never allocates or frees device or
  *     pinned memory: all of it, including the workspace, is owned by the caller and must stay
- *     valid until the work enqueued on it has finished.  The library owns two HIP events.
+ *     valid until the work enqueued on it has finished.  The library owns only HIP events
+ *     (three for ordering streams, plus those of fc_profile_begin).
  *   - Streams are hipStream_t passed as void*; NULL is the default stream.  All calls enqueue work
  *     and return; only FC_PROMOTE_MEMCPY makes the host wait (for the small copy list).
  *   - Every function returns FC_OK (0) or a negative fc_status; fc_last_error gives the text.

@@ -107,7 +107,7 @@ class DecodeSession:
         self.out = torch.zeros((B, cfg.num_q_heads, 128), dtype=torch.float32, device=self.dev)
         self.lse = torch.zeros((B, cfg.num_q_heads), dtype=torch.float32, device=self.dev)
         self.main = torch.cuda.current_stream(self.dev)
-        self.copy = torch.cuda.Stream(self.dev)            # host -> HBM page copies (default priority)
+        self.copy = torch.cuda.Stream(self.dev)            # second stream (default priority): page copies, or the attention that hides them
         # how a rerank step is run (see step()); splitting only pays when the attention is long enough to
         # hide something behind: below ~64 MB per pass the extra launches and the stream hand-overs cost more
         self.overlap = "inline" if cfg.pages_attended() * 8192 >= (64 << 20) else False
