@@ -28,8 +28,8 @@
  * Memory layouts fixed by this ABI (Nmax = max_pages_per_seq, Kmax = max_topk)
  *   q            bf16 [batch][num_q_heads][D]; query head hq belongs to KV head hq / G
  *   kv_pool      bf16 [num_blocks][2][2048]: one physical block = one page of one KV head = 8 KiB,
- *                first the K half, token-major  K[token 0..15][dim 0..127],
- *                then the V half, dim-major     V[dim 0..127][token 0..15]
+ *                first the K half in four 1 KiB chunks of 32 dims: K[chunk 0..3][token 0..15][dim 32*chunk + 0..31],
+ *                then the V half, dim-major:               V[dim 0..127][token 0..15]
  *                (fc_write_kv_pages produces this layout; nothing else needs to know it).
  *                Block 0 is the null block (Sec. 3.4 "Uniformity Through Null Block"): it is never
  *                assigned to a page and its contents are never used.
@@ -231,7 +231,7 @@ int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
  *   - slot == 0: a new page starts.  It takes the LAST block of the head's free list (free_count
  *     decreases by one) and block_table[b][h][page] is set; for a stable head the page also joins
  *     resident_pages (it is being appended to, so it is always a member, Sec. 3.3);
- *   - the token's key goes to row `slot` of the K half and its value to column `slot` of the V half;
+ *   - the token's key goes to token row `slot` of each chunk of the K half and its value to column `slot` of the V half;
  *   - MinMax row of the page (Sec. 3.2): set to the key when slot == 0, else elementwise min / max;
  *   - slot == 15 and the head is stable: the page is now full and is copied, once, to
  *     host_pool[host_block_table[b][h][page]] (Sec. 3.3 "Minimizing Transfer Size"); it stays resident

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(128) void fc_append_kernel(fc_append_params p)
             if (blk > 0) {
                 uint16_t *pg = p.pool + (size_t)blk * FC_PAGE_ELEMS;
                 const uint16_t kx = p.k_new[item * FC_D + d], vx = p.v_new[item * FC_D + d];
-                pg[slot * FC_D + d] = kx;                      // K half, token-major
+                pg[fc_k_elem(slot, d)] = kx;                   // K half, 32-dim chunks of token rows
                 pg[FC_P * FC_D + d * FC_P + slot] = vx;        // V half, dim-major
                 uint16_t *row = p.minmax + (item * (size_t)p.Nmax + page) * (2 * FC_D);
                 if (slot == 0) {

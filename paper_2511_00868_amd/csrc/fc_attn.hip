@@ -14,7 +14,8 @@
 //
 // Matrix-core mapping (wave64, 16x16 tiles; lane = 16*j + n):
 //   S^T[key][query] = K_page[16 x 128] . Q^T[128 x 16]   4 x v_mfma_f32_16x16x32_bf16
-//       A = K rows straight from the page (lane reads 16 B of key row n, dims 32s+8j..+8),
+//       A = K straight from the page: the K half is stored as four 1 KiB chunks of 32 dims, one 64-byte row
+//       per key inside a chunk, so MFMA s reads chunk s as one contiguous 1 KiB (lane: key row n, dims 32s+8j..+8),
 //       B = Q^T, the G real query heads in columns 0..G-1, zero columns after them.
 //       The result leaves lane (n, j) holding keys 4j..4j+3 of query n ...
 //   O^T[dim][query] += V^T[16 dims x 16 keys] . P^T[16 keys x 16 queries]   8 x v_mfma_f32_16x16x16_bf16
@@ -86,7 +87,7 @@ __device__ __forceinline__ void fc_load_page(fc_page_regs &r, const char *pool, 
     const char *base = pool + (size_t)blk * FC_PAGE_BYTES;
 #pragma unroll
     for (int s = 0; s < 4; ++s)
-        r.k[s] = FC_PAGE_LOAD(reinterpret_cast<const bf16x8_t *>(base + lane_k_off + s * 64));
+        r.k[s] = FC_PAGE_LOAD(reinterpret_cast<const bf16x8_t *>(base + lane_k_off + s * 1024));
 #pragma unroll
     for (int c = 0; c < 8; ++c)
         r.v[c] = FC_PAGE_LOAD(reinterpret_cast<const short4_t *>(base + FC_HALF_BYTES + lane_v_off + c * 512));
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(256, FC_ATTN_MIN_WAVES_PER_SIMD) void fc_decode_att
         item = lo;
     }
     const int n = lane & 15, j = lane >> 4;
-    const int lane_k_off = n * 256 + j * 16;
+    const int lane_k_off = n * 64 + j * 16;     // chunk s of the K half: token row n, dims 32s + 8j .. + 8
     const int lane_v_off = n * 32 + j * 8;
 
     while (g0 < g1 && item < items) {

@@ -13,6 +13,11 @@ constexpr int FC_P = 16;           // tokens per page
 constexpr int FC_PAGE_ELEMS = 2 * FC_P * FC_D;        // bf16 elements per block (K half + V half)
 constexpr int FC_PAGE_BYTES = FC_PAGE_ELEMS * 2;      // 8192
 constexpr int FC_HALF_BYTES = FC_PAGE_BYTES / 2;      // 4096
+
+// Element index of K[token t][dim d] inside the K half of a block: four 1 KiB chunks of 32 dims each,
+// inside a chunk one 64-byte row per token.  One matrix-core operand load of the attention kernel
+// (16 tokens x 32 dims) is then one contiguous 1 KiB read, and every 128-byte line is requested once.
+__host__ __device__ __forceinline__ int fc_k_elem(int t, int d) { return (d >> 5) * (FC_P * 32) + t * 32 + (d & 31); }
 constexpr int FC_MM_ROW_BYTES = 2 * FC_D * 2;         // MinMax bytes per page (512)
 constexpr int FC_MAX_PROFILE_EVENTS = 1024;
 constexpr int FC_MAX_ITEMS = 4096;                   // max_batch * num_kv_heads (schedule lives in LDS)

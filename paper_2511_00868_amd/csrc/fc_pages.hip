@@ -1,8 +1,8 @@
 // Support kernels: paged-cache writer (token-major K/V -> pool blocks) and MinMax builder (Sec. 3.2).
 #include "fc_internal.h"
 
-// One workgroup per (page, head).  K half is a straight 4 KiB copy (token-major in both places);
-// the V half is transposed to dim-major through LDS.
+// One workgroup per (page, head).  The K half is written in 16-byte pieces to their places in the
+// chunked layout (fc_k_elem); the V half is transposed to dim-major through LDS.
 __global__ __launch_bounds__(256) void fc_write_pages_kernel(
     const uint16_t *__restrict__ k_src, const uint16_t *__restrict__ v_src, int n_pages,
     const int32_t *__restrict__ block_ids, int ids_stride, uint16_t *__restrict__ pool, long long num_blocks)
@@ -13,8 +13,8 @@ __global__ __launch_bounds__(256) void fc_write_pages_kernel(
     const size_t src_off = ((size_t)h * n_pages + page) * (FC_P * FC_D);
     uint16_t *dst = pool + (size_t)blk * FC_PAGE_ELEMS;
 
-    // K: 256 threads x 16 B
-    reinterpret_cast<uint4 *>(dst)[t] = reinterpret_cast<const uint4 *>(k_src + src_off)[t];
+    // K: 256 threads x 16 B (8 dims of one token, which stay together inside a 32-dim chunk)
+    *reinterpret_cast<uint4 *>(dst + fc_k_elem(t >> 4, (t & 15) * 8)) = reinterpret_cast<const uint4 *>(k_src + src_off)[t];
 
     // V: [16][128] -> [128][16]
     __shared__ uint16_t tile[FC_P][FC_D + 8];
@@ -51,10 +51,10 @@ __global__ __launch_bounds__(128) void fc_minmax_kernel(
     if (blk <= 0 || blk >= num_blocks) return;
     const int ntok = min(FC_P, context_len - page * FC_P);
     const uint16_t *kp = pool + (size_t)blk * FC_PAGE_ELEMS;
-    uint16_t lo = kp[d], hi = lo;
+    uint16_t lo = kp[fc_k_elem(0, d)], hi = lo;
     float flo = __uint_as_float((uint32_t)lo << 16), fhi = flo;
     for (int t = 1; t < ntok; ++t) {
-        uint16_t x = kp[t * FC_D + d];
+        uint16_t x = kp[fc_k_elem(t, d)];
         float f = __uint_as_float((uint32_t)x << 16);
         if (f < flo) { flo = f; lo = x; }
         if (f > fhi) { fhi = f; hi = x; }

@@ -21,8 +21,9 @@ def widen(bits):
 
 
 def native_page(k_page: np.ndarray, v_page: np.ndarray) -> np.ndarray:
-    """The documented block layout, restated: K half token-major [16][128], V half dim-major [128][16]."""
-    return np.concatenate([k_page.reshape(-1), v_page.T.reshape(-1)])
+    """The documented block layout, restated: K half = four chunks of 32 dims, [chunk][token][32];
+    V half dim-major [128][16]."""
+    return np.concatenate([k_page.reshape(16, 4, 32).transpose(1, 0, 2).reshape(-1), v_page.T.reshape(-1)])
 
 
 def audit_sets(gpu_set, ora_set, scores, forced: int) -> None:
@@ -118,7 +119,7 @@ class ParityRun:
             got = sess.kv_pool[blocks].cpu().view(i16).numpy().view(np.uint16)
             for h in range(cfg.num_kv_heads):
                 kp, vp = wl.k[b][h, 16 * p:16 * p + 16], wl.v[b][h, 16 * p:16 * p + 16]
-                np.testing.assert_array_equal(got[h][:ntok * 128], kp.reshape(-1)[:ntok * 128])
+                np.testing.assert_array_equal(got[h][:2048].reshape(4, 16, 32)[:, :ntok], kp.reshape(16, 4, 32).transpose(1, 0, 2)[:, :ntok])
                 np.testing.assert_array_equal(got[h][2048:].reshape(128, 16)[:, :ntok], vp.T[:, :ntok])
         # pages that just filled: the stable heads' host copy holds exactly that page
         host = sess.host_pool.view(i16).numpy().view(np.uint16)
@@ -234,7 +235,7 @@ class ParityRun:
             if ntok == 16:
                 np.testing.assert_array_equal(got[i], exp)
             else:
-                np.testing.assert_array_equal(got[i][:ntok * 128], exp[:ntok * 128])
+                np.testing.assert_array_equal(got[i][:2048].reshape(4, 16, 32)[:, :ntok], exp[:2048].reshape(4, 16, 32)[:, :ntok])
 
     def run(self, steps: Optional[int] = None):
         self.check_minmax()
