@@ -155,6 +155,16 @@ def test_append_reduced_config2_growing_context():
     assert len(r.appended_pages) == 3 * 2      # tokens 4103..4138 start pages 257 and 258 in each sequence
 
 
+def test_append_long_generation_many_new_pages():
+    """A generation of 330 tokens on short ragged contexts: every sequence starts 20 or 21 new pages, fills
+    them, offloads them and meets them again in later reranks."""
+    import dataclasses
+    base = synth.make_config(4, batch=3, ctx=900, steps=331)
+    cfg = dataclasses.replace(base, append_tokens=330, dynamics="static", rerank_interval=5, name="append_long")
+    r = _run(cfg)
+    assert len(r.appended_pages) >= 3 * 20
+
+
 def test_append_paper_variant_growing_context():
     import dataclasses
     cfg = dataclasses.replace(synth.make_config(2, batch=2, ctx=2048 + 15, steps=21), append_tokens=20,
@@ -212,7 +222,7 @@ def test_other_ways_of_running_a_rerank_step(overlap):
     _run(synth.make_config(2, batch=2, ctx=4096 + 7, steps=5), overlap=overlap)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(40))
 def test_random_small_configurations(seed):
     """Shapes nobody chose by hand: batch, head counts, group size, ragged contexts, budgets (some above the
     page count), rerank interval, stable flags, block order, dynamics, growth, wavefront count, promotion
@@ -222,7 +232,7 @@ def test_random_small_configurations(seed):
     batch = int(rng.integers(1, 6))
     Hkv = int(rng.choice([1, 2, 3, 5, 8, 12]))
     G = int(rng.choice([1, 2, 4, 8]))
-    ctx = tuple(int(x) for x in rng.integers(1, 2500, size=batch))
+    ctx = tuple(int(x) for x in rng.integers(1, 2500 if seed < 32 else 12000, size=batch))
     topk = tuple(int(max(1, rng.integers(1, 2 + (-(-c // 16)) * 5 // 4))) for c in ctx)
     stable = tuple(bool(x) for x in rng.integers(0, 2, size=Hkv))
     dynamics = str(rng.choice(["static", "unstable_resample", "drift"]))
