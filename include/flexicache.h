@@ -40,7 +40,8 @@
  *                row 1 per-dim maximum (the MinMax cache of Sec. 3.2), over valid tokens only
  *   topk_pages   int32 [batch][num_kv_heads][Kmax]: ascending logical page ids, -1 padded
  *   topk_count   int32 [batch][num_kv_heads]
- *   context_lens int32 [batch]: tokens in the sequence, >= 1; pages = ceil(len / 16) <= Nmax
+ *   context_lens int32 [batch]: tokens in the sequence; pages = ceil(len / 16) <= Nmax.  0 (or less) is an idle
+ *                slot: no pages, an empty top-K list, nothing promoted, output rows 0 and lse = -inf
  *   stable_flag  uint8 [num_kv_heads] on the HOST: 1 = stable head (profiled offline, Sec. 2.3).  For
  *                fc_rerank_topk it names the heads to rescore; for fc_sparse_decode_attn the heads that
  *                attend over their list instead of over all pages (the paper's own variant, in which the

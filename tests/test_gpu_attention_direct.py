@@ -102,3 +102,37 @@ def test_stable_head_with_budget_one_and_batch_of_three():
         assert all(len(v) == 1 for v in s.selected().values())
     finally:
         s.close()
+
+
+@pytest.mark.parametrize("stable", [(False, False), (True, False)])
+def test_a_sequence_without_tokens_gets_zero_output_and_minus_infinity_lse(stable):
+    """An idle slot of the batch (context length 0) has no pages: its rows are defined (zeros, lse = -inf),
+    the rerank gives it an empty list, nothing is promoted for it, and its neighbours are untouched."""
+    cfg, wl, s = make(333, lambda wl: None, stable=stable, K=3, batch=3)
+    try:
+        q = wl.queries(0)
+        s.set_queries(q)
+        s.context_lens[1] = 0
+        s.out.fill_(7.0)
+        s.lse.fill_(7.0)
+        if any(stable):
+            s.rerank()
+            s.promote()
+        s.attend()
+        s.torch.cuda.synchronize()
+        s.ctx.fc_check_device_state()
+        out, lse = s.out.cpu().numpy().astype(np.float64), s.lse.cpu().numpy().astype(np.float64)
+        assert not out[1].any() and np.all(np.isneginf(lse[1]))
+        if any(stable):
+            assert int(s.topk_count[1, 0]) == 0 and int(s.resident_count[1, 0]) == 0
+            assert int(s.promoted_count[1, 0]) == 0
+        dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, cfg.topk, 1)
+        for b in (0, 2):
+            if any(stable):
+                dec.rerank(b, q[b], oracle.seq_build_minmax(wl.k[b], cfg.ctx[b]))
+            ref, ref_lse = dec.attend(b, q[b], wl.k[b], wl.v[b], override=s.selected())
+            err = np.abs(out[b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
+            assert err.max() <= 2e-3
+            np.testing.assert_allclose(lse[b], ref_lse, rtol=1e-5, atol=2e-3)
+    finally:
+        s.close()
