@@ -58,6 +58,19 @@ def test_group_sizes(Hq, Hkv):
     _run(cfg)
 
 
+def test_sixty_four_kv_heads_and_the_maximum_number_of_items():
+    """64 KV heads (every bit of the head masks) and 512 sequences x 8 heads = 4096 (sequence, head) items, the
+    most one context accepts: the schedule's prefix sums run over 16 rounds of 256 items."""
+    import dataclasses
+    rng = np.random.default_rng(5)
+    base = synth.make_config(1, ctx=700, batch=2, steps=3)
+    _run(dataclasses.replace(base, num_q_heads=64, num_kv_heads=64, stable=tuple(bool(x) for x in rng.integers(0, 2, 64)),
+                             name="heads_64"))
+    ctx = tuple(int(x) for x in rng.integers(1, 90, size=512))
+    _run(dataclasses.replace(synth.make_config(4, batch=512, ctx=64, steps=2), ctx=ctx,
+                             topk=tuple(max(1, -(-c // 16) // 2) for c in ctx), name="items_4096"))
+
+
 def test_few_wavefronts_many_items_per_wavefront():
     # 8 wavefronts over 9 sequences x 8 heads: every wavefront crosses several item boundaries
     _run(synth.make_config(4, batch=9, ctx=3000, steps=2), attn_waves=8)
