@@ -244,7 +244,7 @@ def test_random_small_configurations(seed):
     rng = np.random.default_rng(1000 + seed)
     batch = int(rng.integers(1, 6))
     Hkv = int(rng.choice([1, 2, 3, 5, 8, 12]))
-    G = int(rng.choice([1, 2, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8, 16]))
     ctx = tuple(int(x) for x in rng.integers(1, 2500 if seed < 32 else 12000, size=batch))
     topk = tuple(int(max(1, rng.integers(1, 2 + (-(-c // 16)) * 5 // 4))) for c in ctx)
     stable = tuple(bool(x) for x in rng.integers(0, 2, size=Hkv))
