@@ -215,6 +215,11 @@ def test_free_running_loop_without_host_synchronisation(overlap):
         sel_count = torch.zeros((T,) + tuple(s.resident_count.shape), dtype=torch.int32, device="cuda")
         for t in range(T):
             s.q = q_dev[t]
+            if t % 3 == 1:                      # shift the two streams against each other now and then
+                with torch.cuda.stream(s.copy):
+                    torch.cuda._sleep(150_000)  # ~70 us
+            if t % 5 == 2:
+                torch.cuda._sleep(100_000)
             s.step(t)
             outs[t].copy_(s.out, non_blocking=True)
             sel_pages[t].copy_(s.resident_pages, non_blocking=True)
