@@ -123,9 +123,11 @@ def test_attention_waits_for_delayed_copies_into_poisoned_blocks(mode, overlap):
         s.close()
 
 
-def test_per_sequence_rerank_phases():
+@pytest.mark.parametrize("split", [False, True])
+def test_per_sequence_rerank_phases(split):
     """rerank_mask staggers the sequences (the paper pauses one request at a time, Sec. 3.3): sequence b
-    reranks when (t + b) mod R == 0; the others keep their lists, tables and blocks untouched."""
+    reranks when (t + b) mod R == 0; the others keep their lists, tables and blocks untouched.  With `split`
+    the attention runs as the resident / promoted pair on two streams around in-line copies."""
     import torch
     cfg = synth.make_config(2, batch=4, ctx=2048 + 5, steps=8)
     wl = synth.Workload(dataclasses.replace(cfg, dynamics="static"))
@@ -143,8 +145,13 @@ def test_per_sequence_rerank_phases():
             md = torch.tensor(mask, dtype=torch.uint8, device="cuda")
             before = (s.resident_pages.clone(), s.block_table.clone(), s.free_blocks.clone())
             s.rerank(rerank_mask=md)
-            s.promote(rerank_mask=md)
-            s.attend()
+            if split:
+                s.promote(rerank_mask=md, copy_stream=s.main)
+                s.attend(binding.FC_PAGES_RESIDENT, stream=s.copy)
+                s.attend(binding.FC_PAGES_PROMOTED)
+            else:
+                s.promote(rerank_mask=md)
+                s.attend()
             torch.cuda.synchronize()
             s.ctx.fc_check_device_state()
             sel = s.selected()
