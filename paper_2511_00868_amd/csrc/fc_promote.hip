@@ -40,6 +40,8 @@ struct fc_promote_params {
     int32_t *counters;      // device: [1] = error bits, [2 + parity] = pairs appended, [4] = workgroups done
     int lds_lists;          // both page lists fit in dynamic LDS (2 * Kmax ints)
     int parity;             // calls alternate between two pair counters; each call clears the other one
+    int publish;            // 1: this kernel's last workgroup publishes the pair count (FC_PROMOTE_MEMCPY: the host reads it);
+                            // 0: the gather kernel that follows does, so this kernel ends without a device-wide ticket
     int32_t *host_total;    // pinned, may be NULL
     int32_t *host_total2;   // pinned scratch copy (memcpy mode reads it)
     int list_capacity;
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     if (tid == 0 && p.promoted_count) p.promoted_count[item] = n_prom;
     if (err) atomicOr(&p.counters[1], err);
     // 6. the workgroup that finishes last publishes the pair count and clears the other counter
-    if (tid == 0) {
+    if (tid == 0 && p.publish) {
         __threadfence();
         const int done = atomicAdd(&p.counters[4], 1);
         if (done == (int)(gridDim.x * gridDim.y) - 1) {
@@ -221,11 +223,18 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     }
 }
 
+// pair_count = the counter the recycle kernel before it appended to; other_count = the counter the next
+// call will use, cleared here (the calls alternate between the two, so nothing has to be cleared in between).
 __global__ __launch_bounds__(256) void fc_gather_pages_kernel(const int32_t *__restrict__ copy_list,
-                                                              const int32_t *__restrict__ pair_count, int list_capacity,
+                                                              const int32_t *__restrict__ pair_count, int32_t *other_count,
+                                                              int32_t *host_total, int list_capacity,
                                                               const uint4 *__restrict__ host_pool, uint4 *__restrict__ kv_pool)
 {
     int total = pair_count[0];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (host_total) *host_total = total;
+        *other_count = 0;
+    }
     total = total > list_capacity ? list_capacity : total;
     constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
     for (int i = blockIdx.x; i < total; i += gridDim.x) {
@@ -293,6 +302,7 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     p.num_host_blocks = a->num_host_blocks;
     p.counters = fc_ws_ptr<int32_t>(ctx, ctx->lay.counters);
     p.parity = ctx->promote_calls & 1;
+    p.publish = a->mode == FC_PROMOTE_MEMCPY;
     p.host_total = a->total_promoted;
     p.list_capacity = ctx->max_items * ctx->cfg.max_topk;
     int32_t *scratch_total = reinterpret_cast<int32_t *>(ctx->scratch);
@@ -323,7 +333,7 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     if (a->mode == FC_PROMOTE_GATHER) {
         if (ss != ms) FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
         hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, ss, p.copy_list, p.counters + 2 + p.parity,
-                           p.list_capacity, (const uint4 *)a->host_pool, (uint4 *)a->kv_pool);
+                           p.counters + 2 + (p.parity ^ 1), a->total_promoted, p.list_capacity, (const uint4 *)a->host_pool, (uint4 *)a->kv_pool);
         FC_HIP(ctx, hipGetLastError());
     } else {
         FC_HIP(ctx, hipEventSynchronize(ctx->ev_diff_done));   // the one host wait: for the copy list
