@@ -209,7 +209,8 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     }
     if (tid == 0 && p.promoted_count) p.promoted_count[item] = n_prom;
     if (err) atomicOr(&p.counters[1], err);
-    // 6. the workgroup that finishes last publishes the pair count and clears the other counter
+    // 6. (FC_PROMOTE_MEMCPY only; otherwise the gather kernel does this) the workgroup that finishes last
+    //    publishes the pair count and clears the other counter
     if (tid == 0 && p.publish) {
         __threadfence();
         const int done = atomicAdd(&p.counters[4], 1);
