@@ -106,7 +106,7 @@ def main():
     ap.add_argument("--append", action="store_true",
                     help="grow every context by one token per step (fc_append_kv: page write, MinMax update, offload on fill)")
     ap.add_argument("--no-overlap", action="store_true", help="run rerank, promotion and attention back to back on one stream")
-    ap.add_argument("--overlap-by", choices=["auto", "pages", "heads", "inline", "heads-inline"], default="auto",
+    ap.add_argument("--overlap-by", choices=["auto", "pages", "heads", "inline", "heads-inline", "ride", "heads-ride"], default="auto",
                     help="how a rerank step's attention is split around the page copies")
     ap.add_argument("--cpu-budget", type=float, default=15.0)
     args = ap.parse_args()
@@ -208,7 +208,9 @@ def main():
     ceil_bytes = min(pool_bytes, attention_bytes(cfg, args.paper_unstable_topk)) // 4096 * 4096
     ceil_gbs, ceil_us = sess.ctx.fc_measure_stream_read(sess.kv_pool, ceil_bytes, 16, main)
 
-    inline = sess.overlap in ("inline", "heads-inline")
+    # the paper's variant attends in one pass (every head list-driven), so its copies cannot ride: they run in line
+    ride = sess.overlap in ("ride", "heads-ride") and not args.paper_unstable_topk
+    inline = sess.overlap in ("inline", "heads-inline") or (sess.overlap in ("ride", "heads-ride") and not ride)
     n_rerank = sum(is_rer_timed)
     a_bytes, r_bytes = attention_bytes(cfg, args.paper_unstable_topk), rerank_bytes(cfg)
     step_bytes = a_bytes * args.steps + r_bytes * n_rerank
@@ -242,15 +244,18 @@ def main():
                                                  if plain_us and rr_us else None,
         "rerank_topk_us_per_invocation": round(float(np.median(rr_us)), 2) if rr_us else None,
         "rerank_topk_us_per_step_amortised": round(float(np.median(rr_us)) / cfg.rerank_interval, 2) if rr_us else None,
-        # with the copies in line the recycling kernel and the copies are one enqueue on one stream: only their sum is seen
-        "recycle_us_per_invocation": round(float(np.median(pr_us)), 2) if pr_us and not inline else None,
-        "page_copies_us_per_invocation": round(float(np.median(cp_us)), 2) if cp_us and not inline else None,
+        # with the copies in line the recycling kernel and the copies are one enqueue on one stream: only their sum is
+        # seen; when they ride in an attention launch, "page copies" is that whole launch (resident pages + copies)
+        "recycle_us_per_invocation": round(float(np.median(pr_us)), 2) if pr_us and (ride or not inline) else None,
+        "page_copies_us_per_invocation": round(float(np.median(cp_us)), 2) if cp_us and (ride or not inline) else None,
         "recycle_and_page_copies_us_per_invocation": round(float(np.median(np.add(pr_us, cp_us))), 2) if pr_us else None,
         "rerank_invocations": n_rerank, "promoted_pages_last_rerank": promoted_last,
         "promoted_MB_last_rerank": round(promoted_last * 8192 / 1e6, 2),
         "rerank_step_overlap": {False: "none", True: "by page (resident, then promoted)", "heads": "by head class",
                                 "inline": "by page, copies in line on the main stream, resident pages on the other stream",
-                                "heads-inline": "by head class, copies in line on the main stream, unstable heads on the other stream"}[sess.overlap],
+                                "heads-inline": "by head class, copies in line on the main stream, unstable heads on the other stream",
+                                "ride": "by page, one stream: the copies ride in the launch that attends over the resident pages",
+                                "heads-ride": "by head class, one stream: the copies ride in the unstable heads' launch"}[sess.overlap],
         "roofline": {"bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if args.batch is None and args.ctx is None and not args.paper_unstable_topk and not args.append else None, "kernel": "fc_decode_attn_kernel<FC_HEADS_ALL>",
                      "avg_kernel_us": round(attn_ms * 1e3, 2), "launches": launches,

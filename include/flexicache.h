@@ -157,8 +157,13 @@ int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *args, void *stream);
  *   stream (see head_subset of fc_sparse_decode_attn).
  * mode FC_PROMOTE_GATHER: one kernel on side_stream reads pinned host memory directly; the host
  *   never waits.  mode FC_PROMOTE_MEMCPY: the host waits for the copy list, then issues one
- *   hipMemcpyAsync per page on side_stream. */
-enum { FC_PROMOTE_GATHER = 0, FC_PROMOTE_MEMCPY = 1 };
+ *   hipMemcpyAsync per page on side_stream.  mode FC_PROMOTE_RIDE: single-stream operation; this call
+ *   launches the bookkeeping kernel only, and the copies ride in the next fc_sparse_decode_attn launch on
+ *   main_stream (side_stream is ignored): a FC_PAGES_RESIDENT or FC_HEADS_UNSTABLE call carries them in
+ *   extra workgroups of its own launch, so that they run side by side with that attention and the second
+ *   call of the pair follows in stream order, with no event anywhere; before any other kind of call they
+ *   are launched on their own.  That next attention call must be given main_stream. */
+enum { FC_PROMOTE_GATHER = 0, FC_PROMOTE_MEMCPY = 1, FC_PROMOTE_RIDE = 2 };
 typedef struct {
     const int32_t *new_pages;        /* dev [batch][num_kv_heads][Kmax] (S_t) */
     const int32_t *new_count;        /* dev [batch][num_kv_heads] */
@@ -175,7 +180,7 @@ typedef struct {
     const void *host_pool;           /* pinned */
     int64_t num_host_blocks;
     int32_t batch;
-    int32_t mode;                    /* FC_PROMOTE_GATHER | FC_PROMOTE_MEMCPY */
+    int32_t mode;                    /* FC_PROMOTE_GATHER | FC_PROMOTE_MEMCPY | FC_PROMOTE_RIDE */
     int32_t *promoted_count;         /* dev out [batch][num_kv_heads] or NULL (0 for heads not touched) */
     uint8_t *promoted_flags;         /* dev out [batch][num_kv_heads][Kmax] or NULL: 1 where resident_pages[..][i]
                                         was promoted by this call (all 0 for sequences that did not rerank) */

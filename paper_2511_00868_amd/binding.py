@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("FLEXICACHE_LIB") or os.path.join(HERE, "libflexicache.so")
 
 FC_OK, FC_ERR_INVALID_ARG, FC_ERR_UNSUPPORTED, FC_ERR_WORKSPACE, FC_ERR_HIP, FC_ERR_STATE = 0, -1, -2, -3, -4, -5
-FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY = 0, 1
+FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY, FC_PROMOTE_RIDE = 0, 1, 2
 FC_HEADS_ALL, FC_HEADS_UNSTABLE, FC_HEADS_STABLE, FC_PAGES_RESIDENT, FC_PAGES_PROMOTED = 0, 1, 2, 3, 4
 
 class fc_append_args(C.Structure):

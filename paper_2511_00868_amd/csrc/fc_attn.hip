@@ -59,6 +59,9 @@ struct fc_attn_params {
     float *part_acc;
     float *out;
     float *lse;
+    int attn_blocks;       // workgroups 0 .. attn_blocks-1 attend; any beyond them copy promoted pages (copy_blocks of them)
+    int copy_blocks;
+    fc_copy_job copies;
 };
 
 __device__ __forceinline__ int fc_pages_of(int ctx, int Nmax)
@@ -169,6 +172,13 @@ __device__ __forceinline__ void fc_store_final(const fc_attn_params &p, size_t r
 template <int SUBSET>
 __global__ __launch_bounds__(256, FC_ATTN_MIN_WAVES_PER_SIMD) void fc_decode_attn_kernel(fc_attn_params p)
 {
+    // Page copies riding in this launch (FC_PROMOTE_RIDE): the workgroups behind the attention ones pull the
+    // promoted pages out of host memory while this launch attends over what is already in HBM -- the overlap
+    // of Sec. 3.3 without a second stream and without any event.  One wavefront per copying workgroup.
+    if ((int)blockIdx.x >= p.attn_blocks) {
+        if (threadIdx.x < 64) fc_copy_pages(p.copies, blockIdx.x - p.attn_blocks, p.copy_blocks, threadIdx.x, 64);
+        return;
+    }
     __shared__ int seg[FC_MAX_ITEMS + 1];     // seg[i] = first page of item i in the concatenated order
     __shared__ int wave_tot[4];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -528,6 +538,21 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     // that kernel's is ordered after it here (on its own stream the order is already given)
     if (ctx->diff_valid && stream != ctx->diff_stream) FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_diff_done, 0));
     const bool needs_copies = sub != FC_HEADS_UNSTABLE && sub != FC_PAGES_RESIDENT && (p.active_mask & mask);
+    // copies left by FC_PROMOTE_RIDE: a first call of a pair carries them in its own launch; before any other
+    // call they are launched on their own
+    p.attn_blocks = p.n_waves / 4;
+    p.copy_blocks = 0;
+    p.copies = fc_copy_job{};
+    if (ctx->copies_deferred) {
+        FC_REQUIRE(ctx, stream == ctx->copies_stream, "fc_sparse_decode_attn: after FC_PROMOTE_RIDE the next attention call belongs on fc_promote_pages' main_stream");
+        if (first_of_pair && p.active_mask != 0) {
+            p.copy_blocks = ctx->ride_blocks;
+            p.copies = ctx->deferred;
+        } else {
+            const int st = fc_launch_deferred_copies(ctx, stream);
+            if (st != FC_OK) return st;
+        }
+    }
     if (needs_copies) {   // promoted pages may still be in flight
         const int st = fc_wait_for_copies(ctx, stream);
         if (st != FC_OK) return st;
@@ -537,7 +562,7 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
         bool prof = ctx->profiling && a->head_subset == FC_HEADS_ALL && ctx->prof_used < FC_MAX_PROFILE_EVENTS;
         if (prof) prof = (ctx->prof_seen++ % ctx->prof_stride) == 0;
         if (prof) FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used], s));
-        const dim3 grid(p.n_waves / 4), block(256);
+        const dim3 grid(p.attn_blocks + p.copy_blocks), block(256);
         if (sub == FC_HEADS_ALL) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_ALL>, grid, block, 0, s, p);
         else if (sub == FC_HEADS_UNSTABLE) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_UNSTABLE>, grid, block, 0, s, p);
         else if (sub == FC_HEADS_STABLE) hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_STABLE>, grid, block, 0, s, p);
@@ -548,11 +573,17 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
             ++ctx->prof_used;
         }
     }
-    if (first_of_pair) {
-        FC_HIP(ctx, hipEventRecord(ctx->ev_first_done, s));
-        ctx->first_stream = stream;
+    if (p.copy_blocks) {          // the copies are in flight now, on this stream
+        ctx->copies_deferred = false;
+        ctx->copies_pending = true;
+        ctx->copies_stream = stream;
+        ctx->copies_recorded = false;
     }
-    if (wait_first) FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_first_done, 0));
+    if (first_of_pair) ctx->first_stream = stream;
+    if (wait_first) {   // the event goes behind the first call only now that a second stream turns out to need it
+        FC_HIP(ctx, hipEventRecord(ctx->ev_first_done, (hipStream_t)ctx->first_stream));
+        FC_HIP(ctx, hipStreamWaitEvent(s, ctx->ev_first_done, 0));
+    }
     if (merge_now && merge_mask != 0) {
         p.active_mask = merge_mask;
         hipLaunchKernelGGL(fc_attn_merge_kernel, dim3(p.batch * p.Hkv, p.G), dim3(256), 0, s, p);

@@ -160,10 +160,14 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
     c->diff_valid = false;
     c->pending_pair = 0;
     c->promote_calls = 0;
+    // measured on the 32k-context benchmark (us per step): gather kernel beside the attention launch 16 -> 149,
+    // 32 -> 131, 64 -> 143 workgroups; riding inside the attention launch 24 -> 133, 32 -> 128.4, 40 -> 127.3,
+    // 48 -> 127.3, 56 -> 129.3, 64 -> 131
     c->gather_blocks = 32;
+    c->ride_blocks = 40;
     if (const char *env = getenv("FC_GATHER_BLOCKS")) {
         const int v = atoi(env);
-        if (v >= 1 && v <= 4096) c->gather_blocks = v;
+        if (v >= 1 && v <= 4096) c->gather_blocks = c->ride_blocks = v;
     }
     c->gather_threads = 64;
     if (const char *env = getenv("FC_GATHER_THREADS")) {

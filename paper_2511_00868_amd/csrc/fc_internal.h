@@ -38,6 +38,43 @@ struct fc_ws_layout {
     size_t total;
 };
 
+// Page copies that fc_promote_pages left for the next attention launch (FC_PROMOTE_RIDE).
+struct fc_copy_job {
+    const int32_t *copy_list;    // pairs (host block, pool block)
+    const int32_t *pair_count;   // device counter the recycle kernel appended to
+    int32_t *other_count;        // the counter the next call will use: cleared by the copier
+    int32_t *host_total;         // pinned, may be NULL: receives the pair count
+    int list_capacity;
+    const uint4 *host_pool;
+    uint4 *kv_pool;
+};
+
+// One workgroup's share of the page copies: workgroup `wg` of `n_wg`, its first `threads` (64, 128 or 256)
+// threads; each 8 KiB page is pulled straight out of pinned host memory, four 16 B loads in flight per thread.
+__device__ __forceinline__ void fc_copy_pages(const fc_copy_job &c, int wg, int n_wg, int tid, int threads)
+{
+    int total = c.pair_count[0];
+    if (wg == 0 && tid == 0) {
+        if (c.host_total) *c.host_total = total;
+        *c.other_count = 0;
+    }
+    total = total > c.list_capacity ? c.list_capacity : total;
+    constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
+    for (int i = wg; i < total; i += n_wg) {
+        const long long src = c.copy_list[2 * (size_t)i], dst = c.copy_list[2 * (size_t)i + 1];
+        if (dst <= 0) continue;
+        const uint4 *s = c.host_pool + src * V;
+        uint4 *d = c.kv_pool + dst * V;
+        for (int k = tid; k < V; k += 4 * threads) {
+            const uint4 x0 = s[k], x1 = s[k + threads], x2 = s[k + 2 * threads], x3 = s[k + 3 * threads];
+            d[k] = x0;
+            d[k + threads] = x1;
+            d[k + 2 * threads] = x2;
+            d[k + 3 * threads] = x3;
+        }
+    }
+}
+
 struct fc_ctx {
     fc_config cfg;
     int G;
@@ -58,12 +95,15 @@ struct fc_ctx {
     bool diff_valid;
     void *first_stream;         // stream of the pending first call of a pair
     void *copies_stream;        // stream the pending page copies were enqueued on
+    bool copies_deferred;       // FC_PROMOTE_RIDE: the copies of the last fc_promote_pages have not been launched yet
+    fc_copy_job deferred;
     bool copies_recorded;       // ev_copies_done has been recorded behind them (not done for in-line copies until another stream asks)
     bool copies_pending;
     int pending_pair;        // FC_HEADS_UNSTABLE or FC_PAGES_RESIDENT has left partials for its partner call to merge, else 0
     unsigned promote_calls;
     int gather_threads;   // threads per gather workgroup (64, 128 or 256)
     int gather_blocks;    // workgroups of the host->HBM gather kernel (few and small: see fc_promote.hip)
+    int ride_blocks;      // copying workgroups added to an attention launch (FC_PROMOTE_RIDE)
     // kernel timing
     bool profiling;
     int prof_used;
@@ -74,6 +114,7 @@ struct fc_ctx {
 };
 
 int fc_fail(fc_ctx *ctx, int status, const char *fmt, ...);
+int fc_launch_deferred_copies(fc_ctx *ctx, void *stream);
 int fc_wait_for_copies(fc_ctx *ctx, void *stream);
 int fc_hip_fail(fc_ctx *ctx, hipError_t e, const char *what);
 uint64_t fc_stable_mask(const fc_config &cfg, const uint8_t *stable_flag);

@@ -224,33 +224,22 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     }
 }
 
-// pair_count = the counter the recycle kernel before it appended to; other_count = the counter the next
-// call will use, cleared here (the calls alternate between the two, so nothing has to be cleared in between).
-__global__ __launch_bounds__(256) void fc_gather_pages_kernel(const int32_t *__restrict__ copy_list,
-                                                              const int32_t *__restrict__ pair_count, int32_t *other_count,
-                                                              int32_t *host_total, int list_capacity,
-                                                              const uint4 *__restrict__ host_pool, uint4 *__restrict__ kv_pool)
+__global__ __launch_bounds__(256) void fc_gather_pages_kernel(fc_copy_job job)
 {
-    int total = pair_count[0];
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        if (host_total) *host_total = total;
-        *other_count = 0;
-    }
-    total = total > list_capacity ? list_capacity : total;
-    constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
-    for (int i = blockIdx.x; i < total; i += gridDim.x) {
-        const long long src = copy_list[2 * (size_t)i], dst = copy_list[2 * (size_t)i + 1];
-        if (dst <= 0) continue;
-        const uint4 *s = host_pool + src * V;
-        uint4 *d = kv_pool + dst * V;
-        for (int k = threadIdx.x; k < V; k += 4 * blockDim.x) {   // four 16 B loads in flight per thread
-            const uint4 x0 = s[k], x1 = s[k + blockDim.x], x2 = s[k + 2 * blockDim.x], x3 = s[k + 3 * blockDim.x];
-            d[k] = x0;
-            d[k + blockDim.x] = x1;
-            d[k + 2 * blockDim.x] = x2;
-            d[k + 3 * blockDim.x] = x3;
-        }
-    }
+    fc_copy_pages(job, blockIdx.x, gridDim.x, threadIdx.x, blockDim.x);
+}
+
+// FC_PROMOTE_RIDE copies that no attention launch has carried yet: launched on their own, on `stream`.
+int fc_launch_deferred_copies(fc_ctx *ctx, void *stream)
+{
+    if (!ctx->copies_deferred) return FC_OK;
+    hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, (hipStream_t)stream, ctx->deferred);
+    FC_HIP(ctx, hipGetLastError());
+    ctx->copies_deferred = false;
+    ctx->copies_pending = true;
+    ctx->copies_stream = stream;
+    ctx->copies_recorded = false;
+    return FC_OK;
 }
 
 // Orders `stream` after the page copies of the last fc_promote_pages, if they may still be running.
@@ -277,7 +266,7 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
                "fc_promote_pages: NULL pointer among the required arguments");
     FC_REQUIRE(ctx, a->batch >= 1 && a->batch <= ctx->cfg.max_batch, "fc_promote_pages: batch=%d outside 1..%d", a->batch, ctx->cfg.max_batch);
     FC_REQUIRE(ctx, a->num_pool_blocks >= 2 && a->num_host_blocks >= 1, "fc_promote_pages: pool sizes must be positive");
-    FC_REQUIRE(ctx, a->mode == FC_PROMOTE_GATHER || a->mode == FC_PROMOTE_MEMCPY, "fc_promote_pages: unknown mode %d", a->mode);
+    FC_REQUIRE(ctx, a->mode == FC_PROMOTE_GATHER || a->mode == FC_PROMOTE_MEMCPY || a->mode == FC_PROMOTE_RIDE, "fc_promote_pages: unknown mode %d", a->mode);
 
     fc_promote_params p;
     p.new_pages = a->new_pages;
@@ -309,12 +298,16 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     int32_t *scratch_total = reinterpret_cast<int32_t *>(ctx->scratch);
     p.host_total2 = scratch_total;
     int32_t *scratch_list = reinterpret_cast<int32_t *>(ctx->scratch + 256);
-    p.copy_list = a->mode == FC_PROMOTE_GATHER ? fc_ws_ptr<int32_t>(ctx, ctx->lay.copy_list) : scratch_list;
+    p.copy_list = a->mode != FC_PROMOTE_MEMCPY ? fc_ws_ptr<int32_t>(ctx, ctx->lay.copy_list) : scratch_list;
 
     hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
     if (p.n_stable == 0) {
         if (a->total_promoted) *a->total_promoted = 0;
         return FC_OK;
+    }
+    if (ctx->copies_deferred) {     // copies of an earlier FC_PROMOTE_RIDE call that nothing has carried: they go first
+        const int st = fc_launch_deferred_copies(ctx, main_stream);
+        if (st != FC_OK) return st;
     }
     if (ctx->copies_pending) {
         // copies of an earlier call may still be running on the side stream: this call's bookkeeping
@@ -327,14 +320,34 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), p.lds_lists ? list_bytes : 0, ms, p);
     ++ctx->promote_calls;
     FC_HIP(ctx, hipGetLastError());
-    FC_HIP(ctx, hipEventRecord(ctx->ev_diff_done, ms));
-    ctx->diff_stream = main_stream;
-    ctx->diff_valid = true;
+    if (a->mode == FC_PROMOTE_RIDE) {
+        // single-stream mode: whatever follows on main_stream is ordered behind the recycle kernel by the stream
+        // itself, and an event recorded here would only hold the stream up (a few microseconds)
+        ctx->diff_valid = false;
+    } else {
+        FC_HIP(ctx, hipEventRecord(ctx->ev_diff_done, ms));
+        ctx->diff_stream = main_stream;
+        ctx->diff_valid = true;
+    }
 
+    fc_copy_job job;
+    job.copy_list = p.copy_list;
+    job.pair_count = p.counters + 2 + p.parity;
+    job.other_count = p.counters + 2 + (p.parity ^ 1);
+    job.host_total = a->total_promoted;
+    job.list_capacity = p.list_capacity;
+    job.host_pool = (const uint4 *)a->host_pool;
+    job.kv_pool = (uint4 *)a->kv_pool;
+    if (a->mode == FC_PROMOTE_RIDE) {
+        // nothing is launched here: the next attention launch on main_stream carries the copies
+        ctx->deferred = job;
+        ctx->copies_deferred = true;
+        ctx->copies_stream = main_stream;
+        return FC_OK;
+    }
     if (a->mode == FC_PROMOTE_GATHER) {
         if (ss != ms) FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
-        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, ss, p.copy_list, p.counters + 2 + p.parity,
-                           p.counters + 2 + (p.parity ^ 1), a->total_promoted, p.list_capacity, (const uint4 *)a->host_pool, (uint4 *)a->kv_pool);
+        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, ss, job);
         FC_HIP(ctx, hipGetLastError());
     } else {
         FC_HIP(ctx, hipEventSynchronize(ctx->ev_diff_done));   // the one host wait: for the copy list

@@ -110,7 +110,9 @@ class DecodeSession:
         self.copy = torch.cuda.Stream(self.dev)            # second stream (default priority): page copies, or the attention that hides them
         # how a rerank step is run (see step()); splitting only pays when the attention is long enough to
         # hide something behind: below ~64 MB per pass the extra launches and the stream hand-overs cost more
-        self.overlap = "inline" if cfg.pages_attended() * 8192 >= (64 << 20) else False
+        self.overlap = "ride" if cfg.pages_attended() * 8192 >= (64 << 20) else False
+        if self.overlap == "ride" and promote_mode != binding.FC_PROMOTE_GATHER:
+            self.overlap = "inline"        # per-page hipMemcpyAsync cannot ride in a kernel launch
         self.events = None     # optional dict of torch events a benchmark wants recorded on a rerank step
         self.stable = list(cfg.stable)
         for b in range(B):
@@ -203,7 +205,7 @@ class DecodeSession:
                                 batch=self.cfg.batch, topk_pages=self.resident_pages,
                                 topk_count=self.resident_count, scores_out=self.scores, stream=self.main)
 
-    def promote(self, rerank_mask=None, stream=None, copy_stream=None):
+    def promote(self, rerank_mask=None, stream=None, copy_stream=None, mode=None):
         self.ctx.fc_promote_pages(new_pages=self.topk_pages, new_count=self.topk_count,
                                   resident_pages=self.resident_pages, resident_count=self.resident_count,
                                   block_table=self.block_table, host_block_table=self.host_block_table,
@@ -212,7 +214,7 @@ class DecodeSession:
                                   num_pool_blocks=self.num_pool_blocks, host_pool=self.host_pool,
                                   num_host_blocks=self.num_host_blocks, batch=self.cfg.batch,
                                   main_stream=stream or self.main, side_stream=copy_stream or self.copy,
-                                  mode=self.promote_mode, rerank_mask=rerank_mask,
+                                  mode=self.promote_mode if mode is None else mode, rerank_mask=rerank_mask,
                                   promoted_count=self.promoted_count, promoted_flags=self.promoted_flags,
                                   total_promoted=self.total_promoted)
 
@@ -235,9 +237,14 @@ class DecodeSession:
         heads) to the second stream.  `overlap = True` puts the copies on the second stream instead and
         keeps both attention calls on the main stream (the second waits, on the GPU, for the copies);
         "heads" / "heads-inline" split by head class instead of by page (with "heads-inline" the unstable
-        heads start before the rerank); `overlap = False` does not split."""
+        heads start before the rerank); `overlap = False` does not split.  `overlap = "ride"` needs no second
+        stream at all: promotion leaves the copies to the next attention launch (FC_PROMOTE_RIDE), whose extra
+        workgroups carry them beside the attention over the resident pages; "heads-ride" the same by head class."""
         inline = self.overlap in ("inline", "heads-inline")
-        copy = self.main if inline or not self.overlap else self.copy
+        # "ride": one stream, no events: the copies ride in the launch that attends over the resident pages
+        ride = self.overlap in ("ride", "heads-ride") and self.promote_mode == binding.FC_PROMOTE_GATHER
+        pmode = binding.FC_PROMOTE_RIDE if ride else None
+        copy = self.main if inline or ride or not self.overlap else self.copy
         if self.unstable_topk:
             if not all(self.stable):
                 self.rerank_unstable()
@@ -248,7 +255,7 @@ class DecodeSession:
                 self.rerank()
                 if ev is not None:
                     ev["rerank_end"].record(self.main)
-                self.promote(copy_stream=copy)
+                self.promote(copy_stream=copy, mode=None)
                 if ev is not None:
                     ev["recycle_end"].record(self.main)
                     ev["copies_end"].record(copy)
@@ -266,10 +273,18 @@ class DecodeSession:
             self.rerank()
             if ev is not None:
                 ev["rerank_end"].record(self.main)
-            self.promote(copy_stream=copy)
+            self.promote(copy_stream=copy, mode=pmode)
             if ev is not None:
                 ev["recycle_end"].record(self.main)
-                ev["copies_end"].record(copy)
+                if not ride:
+                    ev["copies_end"].record(copy)
+            if ride:
+                by_head = self.overlap == "heads-ride" and not all(self.stable)
+                self.attend(binding.FC_HEADS_UNSTABLE if by_head else binding.FC_PAGES_RESIDENT)
+                if ev is not None:
+                    ev["copies_end"].record(self.main)     # the launch that carried the copies has ended
+                self.attend(binding.FC_HEADS_STABLE if by_head else binding.FC_PAGES_PROMOTED)
+                return
             if heads_first:
                 self.attend(binding.FC_HEADS_STABLE)
                 return

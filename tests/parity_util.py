@@ -51,7 +51,7 @@ def check_attention(out_gpu: np.ndarray, out_ref: np.ndarray, what: str) -> floa
 
 class ParityRun:
     def __init__(self, cfg: synth.DecodeConfig, *, promote_mode=binding.FC_PROMOTE_GATHER, attn_waves=0,
-                 sample_rows: Optional[int] = None, seed: int = 0, unstable_topk: bool = False, overlap="inline"):
+                 sample_rows: Optional[int] = None, seed: int = 0, unstable_topk: bool = False, overlap="ride"):
         self.cfg = cfg
         self.wl = synth.Workload(cfg)
         self.sess = DecodeSession(cfg, self.wl, promote_mode=promote_mode, attn_waves=attn_waves, keep_scores=True,

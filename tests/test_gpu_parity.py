@@ -226,7 +226,7 @@ def test_one_very_long_sequence_many_partials_per_item():
     _run(cfg)
 
 
-@pytest.mark.parametrize("overlap", [True, "heads", False, "heads-inline"])
+@pytest.mark.parametrize("overlap", [True, "heads", False, "inline", "heads-inline", "heads-ride"])
 def test_other_ways_of_running_a_rerank_step(overlap):
     """The default splits a rerank step by page with the copies in line on the main stream and the resident
     pages on the second stream; copies on the second stream, splitting by head class (either way) and not
@@ -259,4 +259,4 @@ def test_random_small_configurations(seed):
     print(cfg, flush=True)
     _run(cfg, attn_waves=int(rng.choice([0, 4, 16, 64])),
          promote_mode=int(rng.choice([binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_MEMCPY])),
-         overlap=[True, "heads", False, "inline", "heads-inline"][int(rng.integers(0, 5))], unstable_topk=bool(rng.integers(0, 4) == 0))
+         overlap=[True, "heads", False, "inline", "heads-inline", "ride", "heads-ride"][int(rng.integers(0, 7))], unstable_topk=bool(rng.integers(0, 4) == 0))

@@ -200,7 +200,7 @@ def test_stream_read_measurement_reads_in_bounds_and_rejects_bad_arguments():
         ctx.close()
 
 
-@pytest.mark.parametrize("overlap", ["inline", True, "heads", "heads-inline", False])
+@pytest.mark.parametrize("overlap", ["inline", True, "heads", "heads-inline", False, "ride", "heads-ride"])
 def test_free_running_loop_without_host_synchronisation(overlap):
     """The parity harness looks at every step's results, which synchronises the host with the GPU after
     every step and could hide an ordering mistake between consecutive steps (a recycle kernel handing out a
