@@ -208,9 +208,8 @@ def main():
     ceil_bytes = min(pool_bytes, attention_bytes(cfg, args.paper_unstable_topk)) // 4096 * 4096
     ceil_gbs, ceil_us = sess.ctx.fc_measure_stream_read(sess.kv_pool, ceil_bytes, 16, main)
 
-    # the paper's variant attends in one pass (every head list-driven), so its copies cannot ride: they run in line
-    ride = sess.overlap in ("ride", "heads-ride") and not args.paper_unstable_topk
-    inline = sess.overlap in ("inline", "heads-inline") or (sess.overlap in ("ride", "heads-ride") and not ride)
+    ride = sess.overlap in ("ride", "heads-ride")
+    inline = sess.overlap in ("inline", "heads-inline")
     n_rerank = sum(is_rer_timed)
     a_bytes, r_bytes = attention_bytes(cfg, args.paper_unstable_topk), rerank_bytes(cfg)
     step_bytes = a_bytes * args.steps + r_bytes * n_rerank

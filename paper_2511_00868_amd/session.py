@@ -255,10 +255,17 @@ class DecodeSession:
                 self.rerank()
                 if ev is not None:
                     ev["rerank_end"].record(self.main)
-                self.promote(copy_stream=copy, mode=None)
+                self.promote(copy_stream=copy, mode=pmode)
                 if ev is not None:
                     ev["recycle_end"].record(self.main)
-                    ev["copies_end"].record(copy)
+                    if not ride:
+                        ev["copies_end"].record(copy)
+                if ride:       # every head is list-driven here, so the split is by page (entries of unstable heads are never flagged)
+                    self.attend(binding.FC_PAGES_RESIDENT)
+                    if ev is not None:
+                        ev["copies_end"].record(self.main)
+                    self.attend(binding.FC_PAGES_PROMOTED)
+                    return
             self.attend()
             return
         if self.cfg.is_rerank_step(t) and any(self.stable):
