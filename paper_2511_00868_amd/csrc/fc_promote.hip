@@ -9,14 +9,16 @@
 //   promoted pages, in ascending page order, take blocks from the front of that list; table entries
 //   of evicted pages become the null block 0; one (host block, HBM block) pair per promoted page is
 //   appended to a global copy list; the rest of the list becomes the new free list.
-// gather kernel, on the side stream after the recycle kernel: a capped number of small workgroups walk
-//   the copy list and pull each 8 KiB page straight out of pinned host memory -- no host-side gather,
-//   no per-page API call, no host wait.  Its shape is chosen for the kernel that runs beside it: host
-//   reads take microseconds and hold up the memory pipeline of the compute unit they are issued from,
-//   and the attention kernel gives every compute unit an equal share, so it ends with the slowest one.
-//   32 single-wavefront workgroups with four 16 B loads in flight per lane keep PCIe saturated (~55 GB/s)
-//   while touching few compute units (measured rerank step: 286 us; 32 x 256 threads: 318; 256 x 64: 336).  (FC_PROMOTE_MEMCPY instead hands the list to the host, which
-//   issues one hipMemcpyAsync per page.)
+// page copies: a capped number of single-wavefront workgroups walk the copy list and pull each 8 KiB page
+//   straight out of pinned host memory -- no host-side gather, no per-page API call, no host wait.  Three
+//   ways to run them: FC_PROMOTE_RIDE leaves them to the next attention launch, which carries them in extra
+//   workgroups beside its own (one stream, no event; the fastest); FC_PROMOTE_GATHER launches them here as
+//   a kernel of their own, on side_stream or in line on main_stream; FC_PROMOTE_MEMCPY hands the list to the
+//   host, which issues one hipMemcpyAsync per page.  The shape of the copiers is chosen for the attention
+//   that runs beside them: host reads take microseconds, attention runs at about half speed while they are
+//   in flight, and PCIe needs ~128 KiB in flight to stay saturated (~57 GB/s): 32-48 workgroups of one
+//   wavefront with four 16 B loads per lane (measured per step on the 32k-context benchmark: as a kernel of
+//   their own 16 -> 149 us, 32 -> 131, 64 -> 143, 32 x 256 threads -> 190; riding 32 -> 128.4, 40 -> 127.3).
 #include "fc_internal.h"
 
 constexpr int FC_RECYCLE_THREADS = 256;
