@@ -184,8 +184,9 @@ typedef struct {
     int32_t *promoted_count;         /* dev out [batch][num_kv_heads] or NULL (0 for heads not touched) */
     uint8_t *promoted_flags;         /* dev out [batch][num_kv_heads][Kmax] or NULL: 1 where resident_pages[..][i]
                                         was promoted by this call (all 0 for sequences that did not rerank) */
-    int32_t *total_promoted;         /* pinned out (one int32) or NULL: pages copied by this call;
-                                        valid once side_stream has finished (at return for MEMCPY) */
+    int32_t *total_promoted;         /* pinned out (one int32) or NULL: pages copied by this call; valid once
+                                        the copies have finished (side_stream for GATHER; the attention launch
+                                        that carried them for RIDE; at return for MEMCPY) */
 } fc_promote_args;
 int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream, void *side_stream);
 
