@@ -123,11 +123,12 @@ def test_attention_waits_for_delayed_copies_into_poisoned_blocks(mode, overlap):
         s.close()
 
 
-@pytest.mark.parametrize("split", [False, True])
+@pytest.mark.parametrize("split", [False, "two streams", "ride"])
 def test_per_sequence_rerank_phases(split):
     """rerank_mask staggers the sequences (the paper pauses one request at a time, Sec. 3.3): sequence b
     reranks when (t + b) mod R == 0; the others keep their lists, tables and blocks untouched.  With `split`
-    the attention runs as the resident / promoted pair on two streams around in-line copies."""
+    the attention runs as the resident / promoted pair: on two streams around in-line copies, or on one
+    stream with the copies riding in the first launch."""
     import torch
     cfg = synth.make_config(2, batch=4, ctx=2048 + 5, steps=8)
     wl = synth.Workload(dataclasses.replace(cfg, dynamics="static"))
@@ -145,7 +146,11 @@ def test_per_sequence_rerank_phases(split):
             md = torch.tensor(mask, dtype=torch.uint8, device="cuda")
             before = (s.resident_pages.clone(), s.block_table.clone(), s.free_blocks.clone())
             s.rerank(rerank_mask=md)
-            if split:
+            if split == "ride":
+                s.promote(rerank_mask=md, copy_stream=s.main, mode=binding.FC_PROMOTE_RIDE)
+                s.attend(binding.FC_PAGES_RESIDENT)
+                s.attend(binding.FC_PAGES_PROMOTED)
+            elif split:
                 s.promote(rerank_mask=md, copy_stream=s.main)
                 s.attend(binding.FC_PAGES_RESIDENT, stream=s.copy)
                 s.attend(binding.FC_PAGES_PROMOTED)
@@ -254,5 +259,42 @@ def test_free_running_loop_without_host_synchronisation(overlap):
                 err = np.abs(outs[t, b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
                 assert err.max() <= 2e-3, (t, b, err.max())
         print(f"free-running {overlap}: near-tie differences {swaps}")
+    finally:
+        s.close()
+
+
+def test_riding_copies_that_no_pair_carries_are_launched_on_their_own():
+    """FC_PROMOTE_RIDE leaves the copies to the next attention launch.  If that launch is a whole pass
+    (FC_HEADS_ALL) instead of the first call of a pair, or another fc_promote_pages comes first, the
+    library launches them on their own before it; an attention call on another stream is refused."""
+    import torch
+    cfg = synth.make_config(5, batch=2, ctx=4096, steps=9)
+    wl = synth.Workload(cfg)
+    s = DecodeSession(cfg, wl)
+    try:
+        dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable, cfg.topk,
+                                   cfg.rerank_interval)
+        mm = [oracle.seq_build_minmax(wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]
+        for t in range(3):
+            q = wl.queries(t)
+            s.set_queries(q)
+            s.rerank()
+            s.promote(copy_stream=s.main, mode=binding.FC_PROMOTE_RIDE)
+            if t == 1:       # a second promotion with the same lists before any attention: nothing more to promote
+                s.promote(copy_stream=s.main, mode=binding.FC_PROMOTE_RIDE)
+            if t == 2:
+                with pytest.raises(binding.FlexiCacheError) as e:
+                    s.attend(stream=s.copy)
+                assert e.value.status == binding.FC_ERR_INVALID_ARG
+            s.attend()
+            torch.cuda.synchronize()
+            s.ctx.fc_check_device_state()
+            got = s.out.cpu().numpy().astype(np.float64)
+            assert np.all(np.isfinite(got))
+            sel = s.selected()
+            for b in range(cfg.batch):
+                dec.rerank(b, q[b], mm[b])
+                ref, _ = dec.attend(b, q[b], wl.k[b], wl.v[b], override=sel)
+                assert (np.abs(got[b] - ref).max(axis=1) / np.abs(ref).max(axis=1)).max() <= 2e-3
     finally:
         s.close()
