@@ -83,9 +83,26 @@ def cpu_baseline(cfg, wl, budget_s: float = 15.0, unstable_topk: bool = False):
         el = time.perf_counter() - t0
         if el > budget_s:
             break
-    return {"value": round(nbytes / el / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"{steps} whole decode step(s) of {cfg.name} (all {cfg.batch} sequences, rerank every "
-                      f"{cfg.rerank_interval} steps), {el:.1f} s of oracle time", "s_per_step": round(el / steps, 4)}
+    res = {"value": round(nbytes / el / 1e9, 3), "unit": "GB/s", "cores": oracle.threads(), "kind": "oracle",
+           "sample": f"{steps} whole decode step(s) of {cfg.name} (all {cfg.batch} sequences, rerank every "
+                     f"{cfg.rerank_interval} steps), {el:.1f} s of oracle time", "s_per_step": round(el / steps, 4)}
+    if cfg.index in (1, 2) and res["cores"] > 1:
+        # the same oracle on one thread, a few plain steps (attention only, the bulk of a step), about 5 s
+        all_threads = res["cores"]
+        oracle.set_threads(1)
+        t0, n1 = time.perf_counter(), 0
+        while True:
+            q = wl.queries(steps + n1)
+            for b in range(cfg.batch):
+                dec.attend(b, q[b], wl.k[b], wl.v[b])
+            n1 += 1
+            e1 = time.perf_counter() - t0
+            if e1 > budget_s / 3:
+                break
+        oracle.set_threads(all_threads)
+        res["single_thread"] = {"value": round(n1 * attention_bytes(cfg, unstable_topk) / e1 / 1e9, 3), "unit": "GB/s",
+                                "s_per_step": round(e1 / n1, 4), "sample": f"{n1} attention step(s), {e1:.1f} s"}
+    return res
 
 
 def main():

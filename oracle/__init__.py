@@ -52,6 +52,7 @@ def lib():
         L.fco_seq_attention.argtypes = [u16p, u16p, u16p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                         C.c_int, i32p, C.c_int, i32p, C.c_double, f64p, f64p]
         L.fco_threads.restype = C.c_int
+        L.fco_set_threads.argtypes = [C.c_int]
         L.fco_rco.argtypes = [i32p, i32p, C.c_int, C.c_int]
         L.fco_rco.restype = C.c_double
         L.fco_stability.argtypes = [i32p, i32p, C.c_int, C.c_int, C.c_int, C.c_int, f64p]
@@ -73,6 +74,11 @@ def _u16(a) -> np.ndarray:
 
 def threads() -> int:
     return int(lib().fco_threads())
+
+
+def set_threads(n: int) -> None:
+    """Threads for the whole-sequence drivers (timing only: the results do not depend on it)."""
+    lib().fco_set_threads(int(n))
 
 
 # ---- single-head routines -----------------------------------------------------------------------

@@ -254,6 +254,17 @@ void fco_seq_attention(const uint16_t *q, const uint16_t *k, const uint16_t *v, 
     }
 }
 
+/* Number of threads the whole-sequence drivers may use from now on (timing only; results do not depend on
+ * it: every head is computed by one thread).  n <= 0 leaves the setting alone. */
+void fco_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int fco_threads(void)
 {
     int n = 1;
