@@ -205,15 +205,16 @@ def test_stream_read_measurement_reads_in_bounds_and_rejects_bad_arguments():
         ctx.close()
 
 
-@pytest.mark.parametrize("overlap", ["inline", True, "heads", "heads-inline", False, "ride", "heads-ride"])
-def test_free_running_loop_without_host_synchronisation(overlap):
+@pytest.mark.parametrize("overlap,steps", [("inline", 24), (True, 24), ("heads", 24), ("heads-inline", 24), (False, 24),
+                                           ("ride", 24), ("heads-ride", 24), ("ride", 160)])
+def test_free_running_loop_without_host_synchronisation(overlap, steps):
     """The parity harness looks at every step's results, which synchronises the host with the GPU after
     every step and could hide an ordering mistake between consecutive steps (a recycle kernel handing out a
     block that the previous step's attention is still reading, a merge that starts before its partials).
-    Here 24 steps with planted promotions are enqueued back to back; outputs and selections of every step
+    Here 24 (once 160) steps are enqueued back to back; outputs and selections of every step
     are kept on the device and checked against the oracle only afterwards."""
     import torch
-    cfg = synth.make_config(5, batch=3, ctx=8192, steps=24)
+    cfg = synth.make_config(5, batch=3, ctx=8192, steps=steps)
     cfg = dataclasses.replace(cfg, dynamics="static")       # the inputs stay put; the queries alone move the selection
     wl = synth.Workload(cfg)
     s = DecodeSession(cfg, wl)
