@@ -227,87 +227,78 @@ class DecodeSession:
                                        lse=self.lse, head_subset=head_subset, promoted_flags=self.promoted_flags,
                                        stream=stream or self.main)
 
+    def _rerank_and_promote(self, copy, pmode):
+        """Score, select, recycle and the page copies (or, with FC_PROMOTE_RIDE, only their description)."""
+        ev = self.events
+        if ev is not None:
+            ev["rerank_begin"].record(self.main)
+        self.rerank()
+        if ev is not None:
+            ev["rerank_end"].record(self.main)
+        self.promote(copy_stream=copy, mode=pmode)
+        if ev is not None:
+            ev["recycle_end"].record(self.main)
+            if pmode != binding.FC_PROMOTE_RIDE:
+                ev["copies_end"].record(copy)
+
+    def _attend_pair(self, first: int, second: int, first_stream=None, carries_copies=False):
+        """The two attention calls of a split pass; with riding copies the first launch carries them."""
+        self.attend(first, stream=first_stream)
+        if self.events is not None and carries_copies:
+            self.events["copies_end"].record(self.main)     # the launch that carried the copies has ended
+        self.attend(second)
+
     def step(self, t: int):
         """One pass of the hot path for decode step t (queries already set on the main stream).
 
-        On a rerank step scoring, selection and block recycling run first.  `overlap = "inline"` (default)
-        keeps the whole dependent chain (recycling, page copies, attention over the promoted pages, merge)
-        on the main stream with no event between its links, and gives the work that hides the copies
-        (attention over everything already in HBM: all pages of unstable heads, the kept pages of stable
-        heads) to the second stream.  `overlap = True` puts the copies on the second stream instead and
-        keeps both attention calls on the main stream (the second waits, on the GPU, for the copies);
-        "heads" / "heads-inline" split by head class instead of by page (with "heads-inline" the unstable
-        heads start before the rerank); `overlap = False` does not split.  `overlap = "ride"` needs no second
-        stream at all: promotion leaves the copies to the next attention launch (FC_PROMOTE_RIDE), whose extra
-        workgroups carry them beside the attention over the resident pages; "heads-ride" the same by head class."""
-        inline = self.overlap in ("inline", "heads-inline")
-        # "ride": one stream, no events: the copies ride in the launch that attends over the resident pages
-        ride = self.overlap in ("ride", "heads-ride") and self.promote_mode == binding.FC_PROMOTE_GATHER
+        On a rerank step scoring, selection and block recycling run first; `overlap` says how the page
+        copies are hidden.  "ride" (default for all but tiny workloads) needs one stream and no event:
+        promotion leaves the copies to the next attention launch (FC_PROMOTE_RIDE), whose extra workgroups
+        carry them beside the attention over everything already in HBM (all pages of unstable heads, the
+        kept pages of stable heads); a second launch attends over the promoted pages and one merge closes
+        the step.  "inline" runs the copies as a kernel of their own in line on the main stream and gives
+        the resident-page attention to the second stream; True puts the copies on the second stream and
+        keeps both attention calls on the main stream (the second waits, on the GPU, for the copies).
+        "heads-ride" / "heads-inline" / "heads" are the same three with the split by head class instead of
+        by page ("heads-inline" starts the unstable heads before the rerank); False does not split."""
+        mode = self.overlap
+        inline = mode in ("inline", "heads-inline")
+        ride = mode in ("ride", "heads-ride") and self.promote_mode == binding.FC_PROMOTE_GATHER
         pmode = binding.FC_PROMOTE_RIDE if ride else None
-        copy = self.main if inline or ride or not self.overlap else self.copy
+        copy = self.main if inline or ride or not mode else self.copy
+        rerank_now = self.cfg.is_rerank_step(t) and any(self.stable)
+        RES, PRO, UNS, STA = (binding.FC_PAGES_RESIDENT, binding.FC_PAGES_PROMOTED, binding.FC_HEADS_UNSTABLE,
+                              binding.FC_HEADS_STABLE)
         if self.unstable_topk:
+            # the paper's variant: every head is list-driven, the unstable ones rescored at every step; a split can
+            # only be by page (list entries of unstable heads are never flagged as promoted)
             if not all(self.stable):
                 self.rerank_unstable()
-            if self.cfg.is_rerank_step(t) and any(self.stable):
-                ev = self.events
-                if ev is not None:
-                    ev["rerank_begin"].record(self.main)
-                self.rerank()
-                if ev is not None:
-                    ev["rerank_end"].record(self.main)
-                self.promote(copy_stream=copy, mode=pmode)
-                if ev is not None:
-                    ev["recycle_end"].record(self.main)
-                    if not ride:
-                        ev["copies_end"].record(copy)
-                if ride:       # every head is list-driven here, so the split is by page (entries of unstable heads are never flagged)
-                    self.attend(binding.FC_PAGES_RESIDENT)
-                    if ev is not None:
-                        ev["copies_end"].record(self.main)
-                    self.attend(binding.FC_PAGES_PROMOTED)
+            if rerank_now:
+                self._rerank_and_promote(copy, pmode)
+                if ride:
+                    self._attend_pair(RES, PRO, carries_copies=True)
                     return
             self.attend()
             return
-        if self.cfg.is_rerank_step(t) and any(self.stable):
-            ev = self.events
-            heads_first = self.overlap == "heads-inline" and not all(self.stable)
-            if heads_first:
-                # nothing the unstable heads read is touched by the rerank: start them at once, beside it
-                self.copy.wait_stream(self.main)
-                self.attend(binding.FC_HEADS_UNSTABLE, stream=self.copy)
-            if ev is not None:
-                ev["rerank_begin"].record(self.main)
-            self.rerank()
-            if ev is not None:
-                ev["rerank_end"].record(self.main)
-            self.promote(copy_stream=copy, mode=pmode)
-            if ev is not None:
-                ev["recycle_end"].record(self.main)
-                if not ride:
-                    ev["copies_end"].record(copy)
-            if ride:
-                by_head = self.overlap == "heads-ride" and not all(self.stable)
-                self.attend(binding.FC_HEADS_UNSTABLE if by_head else binding.FC_PAGES_RESIDENT)
-                if ev is not None:
-                    ev["copies_end"].record(self.main)     # the launch that carried the copies has ended
-                self.attend(binding.FC_HEADS_STABLE if by_head else binding.FC_PAGES_PROMOTED)
-                return
-            if heads_first:
-                self.attend(binding.FC_HEADS_STABLE)
-                return
-            if inline:
-                self.attend(binding.FC_PAGES_RESIDENT, stream=self.copy)
-                self.attend(binding.FC_PAGES_PROMOTED)
-                return
-            if self.overlap == "heads" and not all(self.stable):
-                self.attend(binding.FC_HEADS_UNSTABLE)
-                self.attend(binding.FC_HEADS_STABLE)
-                return
-            if self.overlap:
-                self.attend(binding.FC_PAGES_RESIDENT)
-                self.attend(binding.FC_PAGES_PROMOTED)
-                return
-        self.attend()
+        if not rerank_now:
+            self.attend()
+            return
+        by_head = mode in ("heads", "heads-inline", "heads-ride") and not all(self.stable)
+        if mode == "heads-inline" and by_head:
+            # nothing the unstable heads read is touched by the rerank: start them at once, beside it
+            self.copy.wait_stream(self.main)
+            self.attend(UNS, stream=self.copy)
+            self._rerank_and_promote(copy, pmode)
+            self.attend(STA)
+            return
+        self._rerank_and_promote(copy, pmode)
+        if not mode:
+            self.attend()
+        elif by_head:
+            self._attend_pair(UNS, STA, carries_copies=ride)
+        else:
+            self._attend_pair(RES, PRO, first_stream=self.copy if inline else None, carries_copies=ride)
 
     def selected(self) -> Dict[Tuple[int, int], np.ndarray]:
         pages = self.resident_pages.cpu().numpy()
