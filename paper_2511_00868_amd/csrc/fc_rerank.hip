@@ -117,6 +117,26 @@ __device__ __forceinline__ uint32_t fc_order_key(float s)
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// One count per participating lane into a 256-bin LDS histogram.  Scores of one head share their sign and
+// most exponent bits, so in the high-digit passes nearly every lane of a wavefront hits the same bin and
+// plain LDS atomics serialise; up to three rounds of "lanes with the first lane's digit add their count
+// with one atomic" take care of the popular bins, the rest add one by one.  Must be called by whole wavefronts.
+__device__ __forceinline__ void fc_hist_add(int *hist, bool on, uint32_t digit)
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int round = 0; round < 3; ++round) {
+        const unsigned long long todo = __ballot(on);
+        if (todo == 0) return;
+        const int leader = __ffsll((long long)todo) - 1;
+        const uint32_t d = __shfl(digit, leader);
+        const unsigned long long same = __ballot(on && digit == d);
+        if (lane == leader) atomicAdd(&hist[d], __popcll(same));
+        if (digit == d) on = false;
+    }
+    if (on) atomicAdd(&hist[digit], 1);
+}
+
 constexpr int FC_SELECT_THREADS = 1024;
 constexpr int FC_SELECT_CACHED = 8;      // keys a thread keeps in registers: up to 8192 pages without re-reading
 
@@ -151,12 +171,13 @@ __device__ __forceinline__ void fc_select_body(const fc_rerank_params &p, const 
 #pragma unroll
                 for (int i = 0; i < FC_SELECT_CACHED; ++i) {
                     const uint32_t k = kreg[i];
-                    if (tid + i * FC_SELECT_THREADS < n && (k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+                    fc_hist_add(hist, tid + i * FC_SELECT_THREADS < n && (k & mask) == prefix, (k >> shift) & 255);
                 }
             } else {
-                for (int pg = tid; pg < n; pg += FC_SELECT_THREADS) {
-                    const uint32_t k = key_at(pg);
-                    if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+                for (int base = 0; base < n; base += FC_SELECT_THREADS) {     // uniform trip count: fc_hist_add votes across the wavefront
+                    const int pg = base + tid;
+                    const uint32_t k = pg < n ? key_at(pg) : 0u;
+                    fc_hist_add(hist, pg < n && (k & mask) == prefix, (k >> shift) & 255);
                 }
             }
             __syncthreads();
