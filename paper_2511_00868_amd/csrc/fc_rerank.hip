@@ -140,8 +140,10 @@ __device__ __forceinline__ void fc_hist_add(int *hist, bool on, uint32_t digit)
 constexpr int FC_SELECT_THREADS = 1024;
 constexpr int FC_SELECT_CACHED = 8;      // keys a thread keeps in registers: up to 8192 pages without re-reading
 
-// CACHED: every thread holds the keys of pages tid + 1024 i (i < 8) in registers, so the four radix
-// passes and the compaction read the scores from memory once instead of five times.
+// CACHED: every thread holds the keys of `per` = ceil(n / 1024) <= 8 consecutive pages in registers, so the
+// four radix passes and the compaction read the scores from memory once instead of five times, and the
+// index-ordered compaction is a walk over a thread's own keys between two workgroup-wide prefix sums (ties,
+// then members).
 template <bool CACHED>
 __device__ __forceinline__ void fc_select_body(const fc_rerank_params &p, const float *score, int32_t *out, int n,
                                                int want, int forced, int *hist, int (*wave_cnt)[FC_SELECT_THREADS / 64],
@@ -150,11 +152,13 @@ __device__ __forceinline__ void fc_select_body(const fc_rerank_params &p, const 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     auto key_at = [&](int pg) -> uint32_t { return pg == forced ? 0xFFFFFFFFu : fc_order_key(score[pg]); };
     uint32_t kreg[FC_SELECT_CACHED];
+    const int per = (n + FC_SELECT_THREADS - 1) / FC_SELECT_THREADS;     // 1..8 when CACHED: pages per thread
+    const int pg0 = tid * per;
     if (CACHED) {
 #pragma unroll
         for (int i = 0; i < FC_SELECT_CACHED; ++i) {
-            const int pg = tid + i * FC_SELECT_THREADS;
-            kreg[i] = pg < n ? key_at(pg) : 0u;
+            const int pg = pg0 + i;
+            kreg[i] = (i < per && pg < n) ? key_at(pg) : 0u;
         }
     }
 
@@ -171,7 +175,7 @@ __device__ __forceinline__ void fc_select_body(const fc_rerank_params &p, const 
 #pragma unroll
                 for (int i = 0; i < FC_SELECT_CACHED; ++i) {
                     const uint32_t k = kreg[i];
-                    fc_hist_add(hist, tid + i * FC_SELECT_THREADS < n && (k & mask) == prefix, (k >> shift) & 255);
+                    if (i < per) fc_hist_add(hist, pg0 + i < n && (k & mask) == prefix, (k >> shift) & 255);
                 }
             } else {
                 for (int base = 0; base < n; base += FC_SELECT_THREADS) {     // uniform trip count: fc_hist_add votes across the wavefront
@@ -244,9 +248,41 @@ __device__ __forceinline__ void fc_select_body(const fc_rerank_params &p, const 
         __syncthreads();
     };
     if (CACHED) {
+        // exclusive prefix sum of one count per thread over the workgroup (threads are in page order)
+        auto scan = [&](int mine, int slot) -> int {
+            int x = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(x, d);
+                if (lane >= d) x += y;
+            }
+            if (lane == 63) wave_cnt[slot][wv] = x;
+            __syncthreads();
+            int before = x - mine;
+            for (int w = 0; w < wv; ++w) before += wave_cnt[slot][w];
+            return before;
+        };
+        int n_eq = 0;
+#pragma unroll
+        for (int i = 0; i < FC_SELECT_CACHED; ++i) n_eq += (i < per && pg0 + i < n && kreg[i] == T) ? 1 : 0;
+        int eq_rank = scan(n_eq, 0);              // ties before this thread's pages
+        bool sel[FC_SELECT_CACHED];
+        int n_sel = 0;
+#pragma unroll
+        for (int i = 0; i < FC_SELECT_CACHED; ++i) {
+            const bool live = i < per && pg0 + i < n;
+            const bool eq = live && kreg[i] == T;
+            sel[i] = (live && kreg[i] > T) || (eq && eq_rank < need_eq);
+            eq_rank += eq ? 1 : 0;
+            n_sel += sel[i] ? 1 : 0;
+        }
+        int pos = scan(n_sel, 1);                 // members before this thread's pages
 #pragma unroll
         for (int i = 0; i < FC_SELECT_CACHED; ++i)
-            if (i * FC_SELECT_THREADS < n) round(tid + i * FC_SELECT_THREADS, kreg[i]);
+            if (sel[i]) {
+                if (pos < p.Kmax) out[pos] = pg0 + i;
+                ++pos;
+            }
     } else {
         for (int base = 0; base < n; base += FC_SELECT_THREADS) {
             const int pg = base + tid;
