@@ -10,8 +10,9 @@
 //
 // Select.  One workgroup per (sequence, stable head): 4-pass 8-bit radix select on the order-
 // preserving integer image of the fp32 score finds the K-th largest key; an index-ordered
-// compaction then emits every page above it plus the lowest-indexed pages equal to it, which is
-// "ties go to the lower page index" and yields the list already ascending.  A partially filled last
+// compaction (two workgroup-wide prefix sums when the keys sit in registers) then emits every page
+// above it plus the lowest-indexed pages equal to it, which is "ties go to the lower page index"
+// and yields the list already ascending.  A partially filled last
 // page gets the largest possible key, so it is always a member and counts toward K (Sec. 3.3).
 #include "fc_internal.h"
 
