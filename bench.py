@@ -237,7 +237,7 @@ def main():
     bytes_per_launch = a_bytes
     ach = bytes_per_launch / (attn_ms * 1e-3) / 1e9 if attn_ms > 0 else 0.0
     out = {
-        "metric": "sparse decode attention effective HBM GB/s (% of peak) + rerank us/step",
+        "metric": "sparse decode attention effective HBM GB/s (% of peak) + rerank \u00b5s/step",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
