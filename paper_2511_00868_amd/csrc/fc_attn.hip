@@ -485,6 +485,8 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     FC_REQUIRE(ctx, a->head_subset < FC_PAGES_RESIDENT || a->promoted_flags, "fc_sparse_decode_attn: FC_PAGES_RESIDENT / FC_PAGES_PROMOTED need promoted_flags");
     const uint64_t mask = fc_stable_mask(ctx->cfg, a->stable_flag);
     FC_REQUIRE(ctx, mask == 0 || (a->topk_pages && a->topk_count), "fc_sparse_decode_attn: stable heads need topk_pages and topk_count");
+    FC_REQUIRE(ctx, !ctx->copies_deferred || stream == ctx->copies_stream,
+               "fc_sparse_decode_attn: after FC_PROMOTE_RIDE the next attention call belongs on fc_promote_pages' main_stream");
     hipStream_t s = (hipStream_t)stream;
 
     fc_attn_params p;
@@ -544,7 +546,6 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     p.copy_blocks = 0;
     p.copies = fc_copy_job{};
     if (ctx->copies_deferred) {
-        FC_REQUIRE(ctx, stream == ctx->copies_stream, "fc_sparse_decode_attn: after FC_PROMOTE_RIDE the next attention call belongs on fc_promote_pages' main_stream");
         if (first_of_pair && p.active_mask != 0) {
             p.copy_blocks = ctx->ride_blocks;
             p.copies = ctx->deferred;
@@ -572,6 +573,7 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
             FC_HIP(ctx, hipEventRecord(ctx->prof_ev[2 * ctx->prof_used + 1], s));
             ++ctx->prof_used;
         }
+        FC_HIP(ctx, hipGetLastError());
     }
     if (p.copy_blocks) {          // the copies are in flight now, on this stream
         ctx->copies_deferred = false;
