@@ -105,6 +105,15 @@ def cpu_baseline(cfg, wl, budget_s: float = 15.0, unstable_topk: bool = False):
     return res
 
 
+def device_facts(torch):
+    """What the runtime says about the GPU the numbers were taken on."""
+    pr = torch.cuda.get_device_properties(0)
+    return {"name": pr.name, "arch": getattr(pr, "gcnArchName", None), "compute_units": pr.multi_processor_count,
+            "hbm_GiB": round(pr.total_memory / 2 ** 30, 1), "l2_per_xcd_MiB": round(getattr(pr, "L2_cache_size", 0) / 2 ** 20, 1),
+            "lds_per_workgroup_KiB": round(getattr(pr, "shared_memory_per_block", 0) / 1024, 1),
+            "wavefront": getattr(pr, "warp_size", None)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -281,6 +290,7 @@ def main():
                      "stream_read_ceiling_bytes": int(ceil_bytes),
                      "frac_of_stream_read_ceiling": round(ach / ceil_gbs, 4) if ceil_gbs > 0 else None},
         "setup_s": round(t_gen, 1),
+        "device": device_facts(torch),
         # the paper's own end-to-end figures, other hardware and a whole serving stack: context, not a comparison
         "paper_context": "FlexiCache paper, 1x NVIDIA H100 94 GB over PCIe 5.0, fp16 KV, against vLLM: up to 70 % less GPU "
                          "KV memory, 1.38-1.55x offline throughput, 1.6-2.1x lower online per-token latency; kernel level: "
