@@ -80,6 +80,8 @@ typedef struct {
     float softmax_scale;       /* 0 -> 1/sqrt(head_dim) */
     int32_t device;            /* HIP device ordinal */
     int32_t attn_waves;        /* 0 -> chosen from the device (wavefronts the attention kernel runs) */
+    int32_t copy_workgroups;   /* 0 -> library default; single-wavefront workgroups that pull promoted pages out of
+                                  pinned host memory (32 as a kernel of their own, 40 riding in an attention launch) */
 } fc_config;
 
 /* Bytes of device workspace / pinned host scratch a context of this shape needs (0 on bad config). */

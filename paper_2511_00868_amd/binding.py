@@ -8,7 +8,7 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("FLEXICACHE_LIB") or os.path.join(HERE, "libflexicache.so")
+LIB_PATH = os.path.join(HERE, "libflexicache.so")
 
 FC_OK, FC_ERR_INVALID_ARG, FC_ERR_UNSUPPORTED, FC_ERR_WORKSPACE, FC_ERR_HIP, FC_ERR_STATE = 0, -1, -2, -3, -4, -5
 FC_PROMOTE_GATHER, FC_PROMOTE_MEMCPY, FC_PROMOTE_RIDE = 0, 1, 2
@@ -38,7 +38,7 @@ class fc_config(C.Structure):
     _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("page_size", C.c_int32), ("max_batch", C.c_int32), ("max_pages_per_seq", C.c_int32),
                 ("max_topk", C.c_int32), ("softmax_scale", C.c_float), ("device", C.c_int32),
-                ("attn_waves", C.c_int32)]
+                ("attn_waves", C.c_int32), ("copy_workgroups", C.c_int32)]
 
 
 class fc_rerank_args(C.Structure):
@@ -129,12 +129,13 @@ class Context:
 
     def __init__(self, *, num_q_heads: int, num_kv_heads: int, max_batch: int, max_pages_per_seq: int,
                  max_topk: int, softmax_scale: float = 0.0, device: int = 0, attn_waves: int = 0,
+                 copy_workgroups: int = 0,
                  head_dim: int = 128, page_size: int = 16):
         import torch
         self.torch = torch
         self.lib = load()
         self.cfg = fc_config(num_q_heads, num_kv_heads, head_dim, page_size, max_batch, max_pages_per_seq,
-                             max_topk, softmax_scale, device, attn_waves)
+                             max_topk, softmax_scale, device, attn_waves, copy_workgroups)
         ws = self.lib.fc_workspace_bytes(C.byref(self.cfg))
         hs = self.lib.fc_host_scratch_bytes(C.byref(self.cfg))
         if ws == 0 or hs == 0:

@@ -29,10 +29,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
 
-#ifndef FC_ATTN_NBUF_VALUE
-#define FC_ATTN_NBUF_VALUE 3
-#endif
-constexpr int FC_ATTN_NBUF = FC_ATTN_NBUF_VALUE;   // pages in flight per wavefront
+constexpr int FC_ATTN_NBUF = 3;   // pages in flight per wavefront
 constexpr int FC_MIN_PAGES_PER_WAVE = 2;
 
 struct fc_attn_params {
@@ -74,11 +71,7 @@ __device__ __forceinline__ int fc_pages_of(int ctx, int Nmax)
 // K/V pages are read once per call and never again before they have long left every cache: the
 // non-temporal hint keeps them from displacing the queries, tables and partials (measured: 104 -> 92 us
 // per call on the 32k-context benchmark).
-#ifdef FC_ATTN_PLAIN_LOADS
-#define FC_PAGE_LOAD(p) (*(p))
-#else
 #define FC_PAGE_LOAD(p) __builtin_nontemporal_load(p)
-#endif
 
 struct fc_page_regs {
     bf16x8_t k[4];
@@ -166,17 +159,14 @@ __device__ __forceinline__ void fc_store_final(const fc_attn_params &p, size_t r
 
 // SUBSET only names the launch (FC_HEADS_ALL ... FC_PAGES_PROMOTED) so that profilers list the kinds
 // of launch, which move very different numbers of bytes, under separate kernel names.
-#ifndef FC_ATTN_MIN_WAVES_PER_SIMD
-#define FC_ATTN_MIN_WAVES_PER_SIMD 2
-#endif
 template <int SUBSET>
-__global__ __launch_bounds__(256, FC_ATTN_MIN_WAVES_PER_SIMD) void fc_decode_attn_kernel(fc_attn_params p)
+__global__ __launch_bounds__(256, 2) void fc_decode_attn_kernel(fc_attn_params p)
 {
     // Page copies riding in this launch (FC_PROMOTE_RIDE): the workgroups behind the attention ones pull the
     // promoted pages out of host memory while this launch attends over what is already in HBM -- the overlap
     // of Sec. 3.3 without a second stream and without any event.  One wavefront per copying workgroup.
     if ((int)blockIdx.x >= p.attn_blocks) {
-        if (threadIdx.x < 64) fc_copy_pages(p.copies, blockIdx.x - p.attn_blocks, p.copy_blocks, threadIdx.x, 64);
+        if (threadIdx.x < FC_COPY_THREADS) fc_copy_pages(p.copies, blockIdx.x - p.attn_blocks, p.copy_blocks, threadIdx.x);
         return;
     }
     __shared__ int seg[FC_MAX_ITEMS + 1];     // seg[i] = first page of item i in the concatenated order

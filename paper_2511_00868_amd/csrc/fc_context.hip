@@ -23,6 +23,7 @@ static int fc_check_config(const fc_config *c, const char **why)
     if (c->max_topk < 1 || c->max_topk > c->max_pages_per_seq) { *why = "max_topk must be in 1..max_pages_per_seq"; return FC_ERR_INVALID_ARG; }
     if (!(c->softmax_scale >= 0.0f) || !isfinite(c->softmax_scale)) { *why = "softmax_scale must be finite and >= 0"; return FC_ERR_INVALID_ARG; }
     if (c->attn_waves < 0 || c->attn_waves > (1 << 16)) { *why = "attn_waves out of range"; return FC_ERR_INVALID_ARG; }
+    if (c->copy_workgroups < 0 || c->copy_workgroups > 4096) { *why = "copy_workgroups out of range"; return FC_ERR_INVALID_ARG; }
     if (c->device < 0) { *why = "device must be >= 0"; return FC_ERR_INVALID_ARG; }
     return FC_OK;
 }
@@ -52,8 +53,6 @@ static void fc_make_layout(const fc_config &c, int attn_waves, fc_ws_layout *l)
 static int fc_resolve_waves(const fc_config *cfg, int num_cus)
 {
     int w = cfg->attn_waves > 0 ? cfg->attn_waves : fc_default_waves(num_cus);
-    const char *env = getenv("FC_ATTN_WAVES");
-    if (cfg->attn_waves == 0 && env && atoi(env) > 0) w = atoi(env);
     w = (w + 3) / 4 * 4;
     return w;
 }
@@ -163,17 +162,8 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
     // measured on the 32k-context benchmark (us per step): gather kernel beside the attention launch 16 -> 149,
     // 32 -> 131, 64 -> 143 workgroups; riding inside the attention launch 24 -> 133, 32 -> 128.4, 40 -> 127.3,
     // 48 -> 127.3, 56 -> 129.3, 64 -> 131
-    c->gather_blocks = 32;
-    c->ride_blocks = 40;
-    if (const char *env = getenv("FC_GATHER_BLOCKS")) {
-        const int v = atoi(env);
-        if (v >= 1 && v <= 4096) c->gather_blocks = c->ride_blocks = v;
-    }
-    c->gather_threads = 64;
-    if (const char *env = getenv("FC_GATHER_THREADS")) {
-        const int v = atoi(env);
-        if (v == 64 || v == 128 || v == 256) c->gather_threads = v;
-    }
+    c->gather_blocks = cfg->copy_workgroups > 0 ? cfg->copy_workgroups : 32;
+    c->ride_blocks = cfg->copy_workgroups > 0 ? cfg->copy_workgroups : 40;
     c->err[0] = 0;
     *out = c;
     return FC_OK;

@@ -49,28 +49,31 @@ struct fc_copy_job {
     uint4 *kv_pool;
 };
 
-// One workgroup's share of the page copies: workgroup `wg` of `n_wg`, its first `threads` (64, 128 or 256)
-// threads; each 8 KiB page is pulled straight out of pinned host memory, four 16 B loads in flight per thread.
-__device__ __forceinline__ void fc_copy_pages(const fc_copy_job &c, int wg, int n_wg, int tid, int threads)
+// One workgroup's share of the page copies: workgroup `wg` of `n_wg`, one wavefront; each 8 KiB page (512 x 16 B)
+// is pulled straight out of pinned host memory in two rounds of four 16 B loads in flight per lane.
+constexpr int FC_COPY_THREADS = 64;
+constexpr int FC_COPY_UNROLL = 4;
+__device__ __forceinline__ void fc_copy_pages(const fc_copy_job &c, int wg, int n_wg, int tid)
 {
+    constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
+    static_assert(V % (FC_COPY_UNROLL * FC_COPY_THREADS) == 0, "a page must be a whole number of copy rounds");
     int total = c.pair_count[0];
     if (wg == 0 && tid == 0) {
         if (c.host_total) *c.host_total = total;
         *c.other_count = 0;
     }
     total = total > c.list_capacity ? c.list_capacity : total;
-    constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
     for (int i = wg; i < total; i += n_wg) {
         const long long src = c.copy_list[2 * (size_t)i], dst = c.copy_list[2 * (size_t)i + 1];
         if (dst <= 0) continue;
         const uint4 *s = c.host_pool + src * V;
         uint4 *d = c.kv_pool + dst * V;
-        for (int k = tid; k < V; k += 4 * threads) {
-            const uint4 x0 = s[k], x1 = s[k + threads], x2 = s[k + 2 * threads], x3 = s[k + 3 * threads];
-            d[k] = x0;
-            d[k + threads] = x1;
-            d[k + 2 * threads] = x2;
-            d[k + 3 * threads] = x3;
+        for (int k = tid; k < V; k += FC_COPY_UNROLL * FC_COPY_THREADS) {
+            uint4 x[FC_COPY_UNROLL];
+#pragma unroll
+            for (int u = 0; u < FC_COPY_UNROLL; ++u) x[u] = s[k + u * FC_COPY_THREADS];
+#pragma unroll
+            for (int u = 0; u < FC_COPY_UNROLL; ++u) d[k + u * FC_COPY_THREADS] = x[u];
         }
     }
 }
@@ -101,7 +104,6 @@ struct fc_ctx {
     bool copies_pending;
     int pending_pair;        // FC_HEADS_UNSTABLE or FC_PAGES_RESIDENT has left partials for its partner call to merge, else 0
     unsigned promote_calls;
-    int gather_threads;   // threads per gather workgroup (64, 128 or 256)
     int gather_blocks;    // workgroups of the host->HBM gather kernel (few and small: see fc_promote.hip)
     int ride_blocks;      // copying workgroups added to an attention launch (FC_PROMOTE_RIDE)
     // kernel timing

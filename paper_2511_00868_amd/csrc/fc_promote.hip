@@ -18,7 +18,7 @@
 //   that runs beside them: host reads take microseconds, attention runs at about half speed while they are
 //   in flight, and PCIe needs ~128 KiB in flight to stay saturated (~57 GB/s): 32-48 workgroups of one
 //   wavefront with four 16 B loads per lane (measured per step on the 32k-context benchmark: as a kernel of
-//   their own 16 -> 149 us, 32 -> 131, 64 -> 143, 32 x 256 threads -> 190; riding 32 -> 128.4, 40 -> 127.3).
+//   their own 16 -> 149 us, 32 -> 131, 64 -> 143; riding 32 -> 128.4, 40 -> 127.3).
 #include "fc_internal.h"
 
 constexpr int FC_RECYCLE_THREADS = 256;
@@ -226,16 +226,16 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     }
 }
 
-__global__ __launch_bounds__(256) void fc_gather_pages_kernel(fc_copy_job job)
+__global__ __launch_bounds__(FC_COPY_THREADS) void fc_gather_pages_kernel(fc_copy_job job)
 {
-    fc_copy_pages(job, blockIdx.x, gridDim.x, threadIdx.x, blockDim.x);
+    fc_copy_pages(job, blockIdx.x, gridDim.x, threadIdx.x);
 }
 
 // FC_PROMOTE_RIDE copies that no attention launch has carried yet: launched on their own, on `stream`.
 int fc_launch_deferred_copies(fc_ctx *ctx, void *stream)
 {
     if (!ctx->copies_deferred) return FC_OK;
-    hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, (hipStream_t)stream, ctx->deferred);
+    hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(FC_COPY_THREADS), 0, (hipStream_t)stream, ctx->deferred);
     FC_HIP(ctx, hipGetLastError());
     ctx->copies_deferred = false;
     ctx->copies_pending = true;
@@ -349,7 +349,7 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     }
     if (a->mode == FC_PROMOTE_GATHER) {
         if (ss != ms) FC_HIP(ctx, hipStreamWaitEvent(ss, ctx->ev_diff_done, 0));
-        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(ctx->gather_threads), 0, ss, job);
+        hipLaunchKernelGGL(fc_gather_pages_kernel, dim3(ctx->gather_blocks), dim3(FC_COPY_THREADS), 0, ss, job);
         FC_HIP(ctx, hipGetLastError());
     } else {
         FC_HIP(ctx, hipEventSynchronize(ctx->ev_diff_done));   // the one host wait: for the copy list
