@@ -232,6 +232,23 @@ typedef struct {
 } fc_attn_args;
 int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *args, void *stream);
 
+/* For callers that cannot allocate device memory at all -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: the whole-pass attention of fc_sparse_decode_attn (head_subset must be
+ * FC_HEADS_ALL) with no context and no workspace.  The schedule and the split partials live in a fixed
+ * array of fc_static_scratch_bytes() (8 MiB) that is part of the library's device image; each GPU holds its
+ * own copy until the process ends.  The call allocates, creates and frees nothing.
+ *   cfg     shapes as for fc_create (max_batch, max_pages_per_seq and max_topk give the strides of the
+ *           tables; attn_waves as there); cfg->device must be the calling thread's current device
+ *   args    as for fc_sparse_decode_attn; promoted_flags is ignored
+ * A shape whose partials do not fit the array ((attn wavefronts + batch * num_kv_heads) * group * 512 B
+ * and a little more: 1024 wavefronts with batch 64 x 8 KV heads x group 4 need 3.3 MB) is refused with
+ * FC_ERR_WORKSPACE.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams, different threads) race; calls on one stream are safe.  Nothing in the array has to
+ * be cleared between calls.  fc_static_last_error gives the text of the calling thread's last failure. */
+int fc_sparse_decode_attn_static(const fc_config *cfg, const fc_attn_args *args, void *stream);
+size_t fc_static_scratch_bytes(void);
+const char *fc_static_last_error(void);
+
 /* ---- decode-time growth of the cache ------------------------------------------------------------- */
 
 /* Appends one new token per sequence (Sec. 2: decoding appends one K/V pair per step) and keeps the

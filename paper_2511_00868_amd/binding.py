@@ -31,7 +31,8 @@ class fc_stability_args(C.Structure):
 EXPORTS = ["fc_workspace_bytes", "fc_host_scratch_bytes", "fc_create", "fc_destroy", "fc_status_string",
            "fc_last_error", "fc_write_kv_pages", "fc_build_minmax", "fc_rerank_topk", "fc_promote_pages",
            "fc_sparse_decode_attn", "fc_append_kv", "fc_offload_pages", "fc_stability_profile", "fc_classify_heads",
-           "fc_check_device_state", "fc_profile_begin", "fc_profile_end", "fc_measure_stream_read"]
+           "fc_check_device_state", "fc_profile_begin", "fc_profile_end", "fc_measure_stream_read",
+           "fc_sparse_decode_attn_static", "fc_static_scratch_bytes", "fc_static_last_error"]
 
 
 class fc_config(C.Structure):
@@ -104,6 +105,11 @@ def load() -> C.CDLL:
         L.fc_profile_end.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int32)]
         L.fc_measure_stream_read.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64, C.c_int32, C.c_void_p,
                                              C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.fc_sparse_decode_attn_static.argtypes = [C.POINTER(fc_config), C.POINTER(fc_attn_args), C.c_void_p]
+        L.fc_static_scratch_bytes.argtypes = []
+        L.fc_static_scratch_bytes.restype = C.c_size_t
+        L.fc_static_last_error.argtypes = []
+        L.fc_static_last_error.restype = C.c_char_p
         _lib = L
     return _lib
 
@@ -121,6 +127,18 @@ def _ptr(t) -> Optional[int]:
 def _host_u8(flags):
     arr = (C.c_uint8 * len(flags))(*[1 if f else 0 for f in flags])
     return arr
+
+
+def fc_sparse_decode_attn_static(cfg: fc_config, *, q, kv_pool, num_pool_blocks: int, block_table, context_lens,
+                                 stable_flag, topk_pages, topk_count, batch: int, out, lse=None, stream=None):
+    """The whole-pass attention without a context or a workspace (the library's built-in scratch array)."""
+    lib = load()
+    flags = _host_u8(stable_flag)
+    a = fc_attn_args(_ptr(q), _ptr(kv_pool), num_pool_blocks, _ptr(block_table), _ptr(context_lens),
+                     C.addressof(flags), _ptr(topk_pages), _ptr(topk_count), batch, _ptr(out), _ptr(lse), FC_HEADS_ALL, None)
+    st = lib.fc_sparse_decode_attn_static(C.byref(cfg), C.byref(a), None if stream is None else stream.cuda_stream)
+    if st != FC_OK:
+        raise FlexiCacheError(st, lib.fc_static_last_error().decode() or lib.fc_status_string(st).decode())
 
 
 class Context:

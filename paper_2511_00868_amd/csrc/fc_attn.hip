@@ -23,6 +23,11 @@
 //       move between lanes.  A = the dim-major V half of the page (lane reads 8 B: dim 16c+n,
 //       keys 4j..4j+3).  P is split into a high and a low bf16 part (two MFMAs) so that PV keeps
 //       ~16 mantissa bits; a single bf16 P would by itself cost 2^-9 relative error.
+#include <math.h>
+#include <stdarg.h>
+
+#include <mutex>
+
 #include "fc_internal.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -581,5 +586,148 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
         hipLaunchKernelGGL(fc_attn_merge_kernel, dim3(p.batch * p.Hkv, p.G), dim3(256), 0, s, p);
     }
     FC_HIP(ctx, hipGetLastError());
+    return FC_OK;
+}
+
+// ---- whole-pass attention for callers that cannot allocate --------------------------------------------
+// Same two kernels as fc_sparse_decode_attn (FC_HEADS_ALL), but the schedule and the split partials live
+// in a fixed array that is part of the library's device image instead of in a caller-supplied workspace,
+// and there is no context: nothing is allocated, created or freed, at set-up or per call.  Every call on
+// a GPU uses that GPU's one copy of the array, so calls that overlap on one GPU race.  Nothing in the
+// array has to start at zero: each call writes its schedule and every partial it later reads.
+constexpr size_t FC_STATIC_SCRATCH_BYTES = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char fc_static_scratch[FC_STATIC_SCRATCH_BYTES];
+
+constexpr int FC_STATIC_MAX_DEVICES = 64;
+struct fc_static_device {
+    bool ready;
+    char *scratch;      // this device's address of fc_static_scratch
+    int num_cus;
+};
+static fc_static_device fc_static_devices[FC_STATIC_MAX_DEVICES];
+static std::mutex fc_static_mutex;
+static thread_local char fc_static_err[256];
+
+static int fc_static_fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(fc_static_err, sizeof fc_static_err, fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+extern "C" const char *fc_static_last_error(void) { return fc_static_err; }
+
+extern "C" size_t fc_static_scratch_bytes(void) { return FC_STATIC_SCRATCH_BYTES; }
+
+// Bytes of the array a call of this shape uses (one schedule, one set of partials).
+static size_t fc_static_layout(int items, int waves, int G, size_t *ml_off, size_t *acc_off)
+{
+    const size_t slots = (size_t)waves + items;
+    size_t off = fc_align_up((size_t)(items + 2) * sizeof(int32_t), 256);
+    *ml_off = off;
+    off = fc_align_up(off + slots * 16 * 2 * sizeof(float), 256);
+    *acc_off = off;
+    off = fc_align_up(off + slots * (size_t)G * FC_D * sizeof(float), 256);
+    return off;
+}
+
+extern "C" int fc_sparse_decode_attn_static(const fc_config *cfg, const fc_attn_args *a, void *stream)
+{
+    fc_static_err[0] = 0;
+    const char *why = nullptr;
+    const int st = fc_check_config(cfg, &why);
+    if (st != FC_OK) return fc_static_fail(st, "fc_sparse_decode_attn_static: %s", why);
+    if (!a) return fc_static_fail(FC_ERR_INVALID_ARG, "fc_sparse_decode_attn_static: args is NULL");
+    if (!(a->q && a->kv_pool && a->block_table && a->context_lens && a->stable_flag && a->out))
+        return fc_static_fail(FC_ERR_INVALID_ARG, "fc_sparse_decode_attn_static: NULL pointer among q, kv_pool, block_table, context_lens, stable_flag, out");
+    if (a->batch < 1 || a->batch > cfg->max_batch)
+        return fc_static_fail(FC_ERR_INVALID_ARG, "fc_sparse_decode_attn_static: batch=%d outside 1..%d", a->batch, cfg->max_batch);
+    if (a->num_pool_blocks < 2) return fc_static_fail(FC_ERR_INVALID_ARG, "fc_sparse_decode_attn_static: num_pool_blocks must be >= 2");
+    if (a->head_subset != FC_HEADS_ALL)
+        return fc_static_fail(FC_ERR_UNSUPPORTED, "fc_sparse_decode_attn_static: only FC_HEADS_ALL (one whole pass) is offered here");
+    const uint64_t mask = fc_stable_mask(*cfg, a->stable_flag);
+    if (mask != 0 && !(a->topk_pages && a->topk_count))
+        return fc_static_fail(FC_ERR_INVALID_ARG, "fc_sparse_decode_attn_static: stable heads need topk_pages and topk_count");
+
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fc_static_fail(FC_ERR_HIP, "fc_sparse_decode_attn_static: hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev != cfg->device || dev >= FC_STATIC_MAX_DEVICES)
+        return fc_static_fail(FC_ERR_INVALID_ARG, "fc_sparse_decode_attn_static: device %d of the configuration must be the current device (%d) and below %d",
+                              cfg->device, dev, FC_STATIC_MAX_DEVICES);
+    fc_static_device d;
+    {
+        std::lock_guard<std::mutex> lock(fc_static_mutex);
+        d = fc_static_devices[dev];
+    }
+    if (!d.ready) {
+        // first call on this device: where this device keeps its copy of the array, and how many compute units it has
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(fc_static_scratch));
+        if (e != hipSuccess || !ptr)
+            return fc_static_fail(FC_ERR_HIP, "fc_sparse_decode_attn_static: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess || cus <= 0)
+            return fc_static_fail(FC_ERR_HIP, "fc_sparse_decode_attn_static: compute-unit count unavailable: %s", hipGetErrorString(e));
+        d.scratch = (char *)ptr;
+        d.num_cus = cus;
+        d.ready = true;
+        std::lock_guard<std::mutex> lock(fc_static_mutex);
+        fc_static_devices[dev] = d;
+    }
+
+    const int G = cfg->num_q_heads / cfg->num_kv_heads;
+    const int waves = fc_resolve_waves(cfg, d.num_cus);
+    const int items = a->batch * cfg->num_kv_heads;
+    size_t ml_off, acc_off;
+    const size_t need = fc_static_layout(items, waves, G, &ml_off, &acc_off);
+    if (need > FC_STATIC_SCRATCH_BYTES)
+        return fc_static_fail(FC_ERR_WORKSPACE, "fc_sparse_decode_attn_static: batch %d x %d KV heads x group %d over %d wavefronts needs %zu bytes of "
+                              "partials, the built-in array holds %zu: use fc_sparse_decode_attn with a workspace", a->batch, cfg->num_kv_heads, G,
+                              waves, need, FC_STATIC_SCRATCH_BYTES);
+
+    const float scale = cfg->softmax_scale > 0.0f ? cfg->softmax_scale : 1.0f / sqrtf((float)FC_D);
+    fc_attn_params p;
+    p.q = (const uint16_t *)a->q;
+    p.pool = (const char *)a->kv_pool;
+    p.num_blocks = a->num_pool_blocks;
+    p.block_table = a->block_table;
+    p.context_lens = a->context_lens;
+    p.topk_pages = a->topk_pages ? a->topk_pages : a->block_table;   // never read when mask == 0
+    p.topk_count = a->topk_count ? a->topk_count : a->context_lens;
+    p.stable_mask = mask;
+    p.active_mask = cfg->num_kv_heads == 64 ? ~0ull : ((1ull << cfg->num_kv_heads) - 1);
+    p.batch = a->batch;
+    p.Hq = cfg->num_q_heads;
+    p.Hkv = cfg->num_kv_heads;
+    p.G = G;
+    p.Nmax = cfg->max_pages_per_seq;
+    p.Kmax = cfg->max_topk;
+    p.n_waves = waves;
+    p.scale_log2 = scale * 1.4426950408889634f;
+    p.seg_start = reinterpret_cast<int32_t *>(d.scratch);
+    p.sched = 0;
+    p.sched_unstable = 0;
+    p.sched_stable = 0;
+    p.stable_both_sets = 0;
+    p.page_filter = 0;
+    p.promoted_flags = nullptr;
+    p.sched_stride = items + 2;
+    p.slot_stride = waves + items;
+    p.part_ml = reinterpret_cast<float *>(d.scratch + ml_off);
+    p.part_acc = reinterpret_cast<float *>(d.scratch + acc_off);
+    p.out = a->out;
+    p.lse = a->lse;
+    p.attn_blocks = waves / 4;
+    p.copy_blocks = 0;
+    p.copies = fc_copy_job{};
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(fc_decode_attn_kernel<FC_HEADS_ALL>, dim3(p.attn_blocks), dim3(256), 0, s, p);
+    hipLaunchKernelGGL(fc_attn_merge_kernel, dim3(items, G), dim3(256), 0, s, p);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fc_static_fail(FC_ERR_HIP, "fc_sparse_decode_attn_static: launch failed: %s", hipGetErrorString(e));
     return FC_OK;
 }

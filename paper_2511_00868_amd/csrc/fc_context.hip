@@ -5,7 +5,7 @@
 
 #include "fc_internal.h"
 
-static int fc_check_config(const fc_config *c, const char **why)
+int fc_check_config(const fc_config *c, const char **why)
 {
     *why = nullptr;
     if (!c) { *why = "config is NULL"; return FC_ERR_INVALID_ARG; }
@@ -50,7 +50,7 @@ static void fc_make_layout(const fc_config &c, int attn_waves, fc_ws_layout *l)
     l->total = off;
 }
 
-static int fc_resolve_waves(const fc_config *cfg, int num_cus)
+int fc_resolve_waves(const fc_config *cfg, int num_cus)
 {
     int w = cfg->attn_waves > 0 ? cfg->attn_waves : fc_default_waves(num_cus);
     w = (w + 3) / 4 * 4;

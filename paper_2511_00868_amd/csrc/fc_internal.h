@@ -116,6 +116,8 @@ struct fc_ctx {
 };
 
 int fc_fail(fc_ctx *ctx, int status, const char *fmt, ...);
+int fc_check_config(const fc_config *c, const char **why);   // FC_OK, or a status with a static text in *why
+int fc_resolve_waves(const fc_config *cfg, int num_cus);     // wavefronts of the attention kernel (a multiple of 4)
 int fc_launch_deferred_copies(fc_ctx *ctx, void *stream);
 int fc_wait_for_copies(fc_ctx *ctx, void *stream);
 int fc_hip_fail(fc_ctx *ctx, hipError_t e, const char *what);
