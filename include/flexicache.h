@@ -192,6 +192,15 @@ typedef struct {
 } fc_promote_args;
 int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream, void *side_stream);
 
+/* fc_rerank_topk followed by fc_promote_pages as one call, with the same results bit for bit.  Up to 8192 pages per
+ * sequence and a page budget of up to 4096 the selection of a head and the recycling of its blocks then run in one
+ * kernel (the fused recycling kernel of Sec. 3.4 "Physical Block Reuse During Reranking"), which takes two launches
+ * and one trip of the new lists through memory off the path to the page copies; other shapes run the same kernels
+ * as the two separate calls.  rerank->topk_pages / topk_count must be promote->new_pages / new_count, and batch,
+ * rerank_mask and stable_flag must agree; everything else as documented for the two calls. */
+int fc_rerank_promote(fc_ctx *ctx, const fc_rerank_args *rerank, const fc_promote_args *promote, void *main_stream,
+                      void *side_stream);
+
 /* Head-heterogeneous paged decode attention (Sec. 3.1; split-KV decode attention as in Sec. 4.1).
  * For every sequence b and KV head h the page set is topk_pages[b][h][0..topk_count) if the head is
  * stable, all pages 0..ceil(context_len/16)-1 otherwise; each of the G query heads of the group gets

@@ -32,7 +32,7 @@ EXPORTS = ["fc_workspace_bytes", "fc_host_scratch_bytes", "fc_create", "fc_destr
            "fc_last_error", "fc_write_kv_pages", "fc_build_minmax", "fc_rerank_topk", "fc_promote_pages",
            "fc_sparse_decode_attn", "fc_append_kv", "fc_offload_pages", "fc_stability_profile", "fc_classify_heads",
            "fc_check_device_state", "fc_profile_begin", "fc_profile_end", "fc_measure_stream_read",
-           "fc_sparse_decode_attn_static", "fc_static_scratch_bytes", "fc_static_last_error"]
+           "fc_sparse_decode_attn_static", "fc_static_scratch_bytes", "fc_static_last_error", "fc_rerank_promote"]
 
 
 class fc_config(C.Structure):
@@ -95,6 +95,7 @@ def load() -> C.CDLL:
         L.fc_rerank_topk.argtypes = [C.c_void_p, C.POINTER(fc_rerank_args), C.c_void_p]
         L.fc_promote_pages.argtypes = [C.c_void_p, C.POINTER(fc_promote_args), C.c_void_p, C.c_void_p]
         L.fc_sparse_decode_attn.argtypes = [C.c_void_p, C.POINTER(fc_attn_args), C.c_void_p]
+        L.fc_rerank_promote.argtypes = [C.c_void_p, C.POINTER(fc_rerank_args), C.POINTER(fc_promote_args), C.c_void_p, C.c_void_p]
         L.fc_append_kv.argtypes = [C.c_void_p, C.POINTER(fc_append_args), C.c_void_p]
         L.fc_offload_pages.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32,
                                        C.c_void_p]
@@ -220,6 +221,21 @@ class Context:
                             num_host_blocks, batch, mode, _ptr(promoted_count), _ptr(promoted_flags), _ptr(total_promoted))
         self._check(self.lib.fc_promote_pages(self.handle, C.byref(a), self._stream(main_stream),
                                               self._stream(side_stream)))
+
+    def fc_rerank_promote(self, *, q, minmax, context_lens, stable_flag, k_per_seq, batch: int, topk_pages, topk_count,
+                          resident_pages, resident_count, block_table, host_block_table, free_blocks, free_count,
+                          kv_pool, num_pool_blocks: int, host_pool, num_host_blocks: int, main_stream, side_stream,
+                          mode: int = FC_PROMOTE_GATHER, rerank_mask=None, scores_out=None, promoted_count=None,
+                          promoted_flags=None, total_promoted=None):
+        flags = _host_u8(stable_flag)
+        r = fc_rerank_args(_ptr(q), _ptr(minmax), _ptr(context_lens), C.addressof(flags), _ptr(k_per_seq),
+                           _ptr(rerank_mask), batch, _ptr(topk_pages), _ptr(topk_count), _ptr(scores_out))
+        a = fc_promote_args(_ptr(topk_pages), _ptr(topk_count), _ptr(resident_pages), _ptr(resident_count),
+                            _ptr(block_table), _ptr(host_block_table), _ptr(free_blocks), _ptr(free_count),
+                            C.addressof(flags), _ptr(rerank_mask), _ptr(kv_pool), num_pool_blocks, _ptr(host_pool),
+                            num_host_blocks, batch, mode, _ptr(promoted_count), _ptr(promoted_flags), _ptr(total_promoted))
+        self._check(self.lib.fc_rerank_promote(self.handle, C.byref(r), C.byref(a), self._stream(main_stream),
+                                               self._stream(side_stream)))
 
     def fc_sparse_decode_attn(self, *, q, kv_pool, num_pool_blocks: int, block_table, context_lens, stable_flag,
                               topk_pages, topk_count, batch: int, out, lse=None, head_subset: int = FC_HEADS_ALL,

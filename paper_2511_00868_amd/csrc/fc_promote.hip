@@ -19,67 +19,41 @@
 //   in flight, and PCIe needs ~128 KiB in flight to stay saturated (~57 GB/s): 32-48 workgroups of one
 //   wavefront with four 16 B loads per lane (measured per step on the 32k-context benchmark: as a kernel of
 //   their own 16 -> 149 us, 32 -> 131, 64 -> 143; riding 32 -> 128.4, 40 -> 127.3).
-#include "fc_internal.h"
+#include "fc_recycle.h"
 
 constexpr int FC_RECYCLE_THREADS = 256;
 
-struct fc_promote_params {
-    const int32_t *new_pages;
-    const int32_t *new_count;
-    int32_t *resident_pages;
-    int32_t *resident_count;
-    int32_t *block_table;
-    const int32_t *host_block_table;
-    int32_t *free_blocks;
-    int32_t *free_count;
-    const uint8_t *rerank_mask;
-    int32_t *promoted_count;
-    uint8_t *promoted_flags;
-    int batch, Hkv, Nmax, Kmax, n_stable;
-    uint8_t heads[64];
-    long long num_pool_blocks, num_host_blocks;
-    int32_t *copy_list;     // device or pinned: pairs (host block, pool block)
-    int32_t *counters;      // device: [1] = error bits, [2 + parity] = pairs appended, [4] = workgroups done
-    int lds_lists;          // both page lists fit in dynamic LDS (2 * Kmax ints)
-    int parity;             // calls alternate between two pair counters; each call clears the other one
-    int publish;            // 1: this kernel's last workgroup publishes the pair count (FC_PROMOTE_MEMCPY: the host reads it);
-                            // 0: the gather kernel that follows does, so this kernel ends without a device-wide ticket
-    int32_t *host_total;    // pinned, may be NULL
-    int32_t *host_total2;   // pinned scratch copy (memcpy mode reads it)
-    int list_capacity;
-};
-
-__device__ __forceinline__ bool fc_sorted_contains(const int32_t *a, int n, int x)
+// Exclusive prefix count over the 256 threads of the fallback kernel below.
+__device__ __forceinline__ int fc_block_rank256(bool flag, int *wave_cnt, int &total)
 {
-    int lo = 0, hi = n;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        const int v = a[mid];
-        if (v == x) return true;
-        if (v < x) lo = mid + 1; else hi = mid;
-    }
-    return false;
+    return fc_block_rank<FC_RECYCLE_THREADS>(flag, wave_cnt, total);
 }
 
-// Exclusive prefix count of `flag` over the workgroup; `total` gets the workgroup sum.
-__device__ __forceinline__ int fc_block_rank(bool flag, int *wave_cnt, int &total)
-{
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const unsigned long long bal = __ballot(flag);
-    if (lane == 0) wave_cnt[wv] = __popcll(bal);
-    __syncthreads();
-    int before = 0;
-    total = 0;
-    for (int k = 0; k < FC_RECYCLE_THREADS / 64; ++k) {
-        const int c = wave_cnt[k];
-        if (k < wv) before += c;
-        total += c;
-    }
-    __syncthreads();
-    return before + __popcll(bal & ((1ull << lane) - 1ull));
-}
-
+// The usual kernel: one workgroup per (sequence, stable head), all three lists in LDS (3 * Kmax ints).
 __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promote_params p)
+{
+    __shared__ int wave_cnt[FC_RECYCLE_THREADS / 64 + 1];
+    extern __shared__ int32_t lists[];
+    const int b = blockIdx.y;
+    const int h = p.heads[blockIdx.x];
+    const size_t item = (size_t)b * p.Hkv + h;
+    const int tid = threadIdx.x;
+    const bool skip = p.rerank_mask && !p.rerank_mask[b];
+    int n_old = 0, n_new = 0, n_free = 0;
+    if (!skip) { n_old = p.resident_count[item]; n_new = p.new_count[item]; n_free = p.free_count[item]; }
+    n_old = min(max(n_old, 0), p.Kmax);
+    n_new = min(max(n_new, 0), p.Kmax);
+    n_free = min(max(n_free, 0), p.Kmax);
+    const int32_t *old_g = p.resident_pages + item * (size_t)p.Kmax;
+    const int32_t *new_g = p.new_pages + item * (size_t)p.Kmax;
+    for (int i = tid; i < n_old; i += FC_RECYCLE_THREADS) lists[i] = old_g[i];
+    for (int i = tid; i < n_new; i += FC_RECYCLE_THREADS) lists[p.Kmax + i] = new_g[i];
+    __syncthreads();
+    fc_recycle_body<FC_RECYCLE_THREADS>(p, item, skip, n_old, n_new, n_free, lists, wave_cnt);
+}
+
+// Fallback for page budgets whose lists do not fit in LDS: the same steps on the lists in global memory.
+__global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_global_kernel(fc_promote_params p)
 {
     __shared__ int wave_cnt[FC_RECYCLE_THREADS / 64];
     __shared__ int sh_list_base;
@@ -95,16 +69,8 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
     n_free = min(max(n_free, 0), p.Kmax);
     int32_t *old_g = p.resident_pages + item * (size_t)p.Kmax;
     const int32_t *new_g = p.new_pages + item * (size_t)p.Kmax;
-    // both lists go to LDS when they fit: the binary searches below are chains of dependent reads
-    extern __shared__ int32_t lists[];
-    const bool in_lds = p.lds_lists != 0;
-    if (in_lds) {
-        for (int i = tid; i < n_old; i += FC_RECYCLE_THREADS) lists[i] = old_g[i];
-        for (int i = tid; i < n_new; i += FC_RECYCLE_THREADS) lists[p.Kmax + i] = new_g[i];
-        __syncthreads();
-    }
-    const int32_t *old_l = in_lds ? lists : old_g;
-    const int32_t *new_l = in_lds ? lists + p.Kmax : new_g;
+    const int32_t *old_l = old_g;
+    const int32_t *new_l = new_g;
     int32_t *tbl = p.block_table + item * (size_t)p.Nmax;
     const int32_t *htbl = p.host_block_table + item * (size_t)p.Nmax;
     int32_t *fb = p.free_blocks + item * (size_t)p.Kmax;
@@ -121,7 +87,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
             ev = page >= 0 && page < p.Nmax && !fc_sorted_contains(new_l, n_new, page);
         }
         int tot;
-        const int r = fc_block_rank(ev, wave_cnt, tot);
+        const int r = fc_block_rank256(ev, wave_cnt, tot);
         if (ev) {
             if (pool + r < p.Kmax) fb[pool + r] = tbl[page]; else err |= FC_DEV_ERR_FREE_OVERFLOW;
             tbl[page] = 0;
@@ -142,7 +108,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
             pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
         }
         int tot;
-        fc_block_rank(pr, wave_cnt, tot);
+        fc_block_rank256(pr, wave_cnt, tot);
         n_prom += tot;
     }
     if (tid == 0) sh_list_base = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
@@ -160,7 +126,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_kernel(fc_promo
             pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
         }
         int tot;
-        const int r = taken + fc_block_rank(pr, wave_cnt, tot);
+        const int r = taken + fc_block_rank256(pr, wave_cnt, tot);
         if (p.promoted_flags && i < n_new) p.promoted_flags[item * (size_t)p.Kmax + i] = pr ? 1 : 0;
         if (pr) {
             if (r < pool) {
@@ -259,9 +225,10 @@ int fc_wait_for_copies(fc_ctx *ctx, void *stream)
     return FC_OK;
 }
 
-extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *main_stream, void *side_stream)
+// fc_promote_pages, optionally preceded by the scoring and selection of `rerank` (fc_rerank_promote): the selection
+// then recycles each head's blocks in its own kernel when the shapes allow it.
+static int fc_promote_impl(fc_ctx *ctx, const fc_promote_args *a, void *main_stream, void *side_stream, const fc_rerank_args *rerank)
 {
-    if (!ctx) return FC_ERR_INVALID_ARG;
     FC_REQUIRE(ctx, a, "fc_promote_pages: args is NULL");
     FC_REQUIRE(ctx, a->new_pages && a->new_count && a->resident_pages && a->resident_count && a->block_table &&
                         a->host_block_table && a->free_blocks && a->free_count && a->stable_flag && a->kv_pool && a->host_pool,
@@ -307,6 +274,13 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
         if (a->total_promoted) *a->total_promoted = 0;
         return FC_OK;
     }
+    if (rerank) {
+        FC_REQUIRE(ctx, rerank->topk_pages == a->new_pages && rerank->topk_count == a->new_count && rerank->batch == a->batch &&
+                            rerank->rerank_mask == a->rerank_mask && rerank->stable_flag &&
+                            fc_stable_mask(ctx->cfg, rerank->stable_flag) == fc_stable_mask(ctx->cfg, a->stable_flag),
+                   "fc_rerank_promote: the selection's outputs must be the promotion's new_pages / new_count, with the same batch, "
+                   "rerank_mask and stable_flag");
+    }
     if (ctx->copies_deferred) {     // copies of an earlier FC_PROMOTE_RIDE call that nothing has carried: they go first
         const int st = fc_launch_deferred_copies(ctx, main_stream);
         if (st != FC_OK) return st;
@@ -317,9 +291,19 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
         const int st = fc_wait_for_copies(ctx, main_stream);
         if (st != FC_OK) return st;
     }
-    const size_t list_bytes = 2 * (size_t)p.Kmax * sizeof(int32_t);
-    p.lds_lists = list_bytes <= 48 * 1024;
-    hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), p.lds_lists ? list_bytes : 0, ms, p);
+    const size_t list_bytes = 3 * (size_t)p.Kmax * sizeof(int32_t);
+    p.lds_lists = list_bytes <= FC_RECYCLE_MAX_LDS;
+    bool fused = false;
+    if (rerank) {
+        const int st = fc_rerank_launch(ctx, rerank, &p, ms, &fused);
+        if (st != FC_OK) return st;
+    }
+    if (fused)
+        ;   // the selection kernel has recycled the blocks
+    else if (p.lds_lists)
+        hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), list_bytes, ms, p);
+    else
+        hipLaunchKernelGGL(fc_recycle_global_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), 0, ms, p);
     ++ctx->promote_calls;
     FC_HIP(ctx, hipGetLastError());
     if (a->mode == FC_PROMOTE_RIDE) {
@@ -370,4 +354,18 @@ extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *mai
     ctx->copies_pending = true;
     ctx->copies_stream = side_stream;
     return FC_OK;
+}
+
+extern "C" int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *a, void *main_stream, void *side_stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    return fc_promote_impl(ctx, a, main_stream, side_stream, nullptr);
+}
+
+extern "C" int fc_rerank_promote(fc_ctx *ctx, const fc_rerank_args *rerank, const fc_promote_args *promote, void *main_stream,
+                                 void *side_stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    FC_REQUIRE(ctx, rerank, "fc_rerank_promote: rerank args is NULL");
+    return fc_promote_impl(ctx, promote, main_stream, side_stream, rerank);
 }

@@ -14,13 +14,20 @@
 // above it plus the lowest-indexed pages equal to it, which is "ties go to the lower page index"
 // and yields the list already ascending.  A partially filled last
 // page gets the largest possible key, so it is always a member and counts toward K (Sec. 3.3).
-#include "fc_internal.h"
+//
+// Up to 8192 pages per sequence the K-th key is found faster than by radix passes: the scores of the candidates are
+// spread linearly over a few hundred to two thousand bins between their minimum and maximum (a monotone map, so
+// bins order the keys), one histogram and one scan find the bin that holds the K-th largest, and the handful of
+// candidates in that bin are ranked against each other directly; a crowded bin (outliers, long runs of ties) is
+// refined the same way, and a bin of equal scores ends the search (ties to the lower index).  The same kernel can
+// go on to recycle the head's blocks (fc_rerank_promote; the fused kernel of Sec. 3.4).
+#include "fc_recycle.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
 
-constexpr int FC_SCORE_TILES_PER_WAVE = 4;                 // 16-page tiles per wavefront
+constexpr int FC_SCORE_TILES_PER_WAVE = 4;                 // 16-page tiles per wavefront, all in flight at once
 constexpr int FC_SCORE_PAGES_PER_BLOCK = 4 * FC_SCORE_TILES_PER_WAVE * 16;
 
 struct fc_rerank_params {
@@ -38,12 +45,13 @@ struct fc_rerank_params {
 
 struct fc_mm_regs { bf16x8_t a[8]; };
 
+// MinMax rows are read once per rerank and not again before they have left every cache: non-temporal loads.
 __device__ __forceinline__ void fc_load_mm_tile(fc_mm_regs &r, const char *rows, int page, int last_page, int j)
 {
     const int pg = page > last_page ? last_page : page;
     const char *src = rows + (size_t)pg * FC_MM_ROW_BYTES + j * 16;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) r.a[s] = *reinterpret_cast<const bf16x8_t *>(src + s * 64);
+    for (int s = 0; s < 8; ++s) r.a[s] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t *>(src + s * 64));
 }
 
 __global__ __launch_bounds__(256) void fc_score_kernel(fc_rerank_params p)
@@ -58,6 +66,17 @@ __global__ __launch_bounds__(256) void fc_score_kernel(fc_rerank_params p)
     const int page0 = blockIdx.x * FC_SCORE_PAGES_PER_BLOCK + wave * (FC_SCORE_TILES_PER_WAVE * 16);
     if (page0 >= n_pages) return;
     const int lane = threadIdx.x & 63, n = lane & 15, j = lane >> 4;
+    const size_t item = (size_t)b * p.Hkv + h;
+    const char *rows = p.minmax + item * (size_t)p.Nmax * FC_MM_ROW_BYTES;
+    float *score = p.scores + item * (size_t)p.Nmax;
+    const int last_page = n_pages - 1;
+
+    // every load of this wavefront's pages (32 KiB) is issued before anything waits on one: the kernel is one
+    // memory round trip deep after the context length
+    fc_mm_regs buf[FC_SCORE_TILES_PER_WAVE];
+#pragma unroll
+    for (int t = 0; t < FC_SCORE_TILES_PER_WAVE; ++t)
+        if (page0 + 16 * t < n_pages) fc_load_mm_tile(buf[t], rows, page0 + 16 * t + n, last_page, j);
 
     // B operand: k index 0..127 pairs kmin with q-, 128..255 pairs kmax with q+.
     bf16x8_t qb[8];
@@ -77,22 +96,13 @@ __global__ __launch_bounds__(256) void fc_score_kernel(fc_rerank_params p)
             qb[s + 4] = __builtin_bit_cast(bf16x8_t, pos);
         }
     }
-    const size_t item = (size_t)b * p.Hkv + h;
-    const char *rows = p.minmax + item * (size_t)p.Nmax * FC_MM_ROW_BYTES;
-    float *score = p.scores + item * (size_t)p.Nmax;
-    const int last_page = n_pages - 1;
-
-    fc_mm_regs buf[2];
-    fc_load_mm_tile(buf[0], rows, page0 + n, last_page, j);
 #pragma unroll
     for (int t = 0; t < FC_SCORE_TILES_PER_WAVE; ++t) {
         const int pg = page0 + 16 * t;
         if (pg >= n_pages) break;
-        if (t + 1 < FC_SCORE_TILES_PER_WAVE && pg + 16 < n_pages)
-            fc_load_mm_tile(buf[(t + 1) & 1], rows, pg + 16 + n, last_page, j);
         float4_t s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int k = 0; k < 8; ++k) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[t & 1].a[k], qb[k], s, 0, 0, 0);
+        for (int k = 0; k < 8; ++k) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(buf[t].a[k], qb[k], s, 0, 0, 0);
         // lane (n, j) holds pages pg + 4j + v of query n: maximum over the G queries of the group
         for (int d = 1; d < p.G; d <<= 1) {
 #pragma unroll
@@ -320,9 +330,225 @@ __global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_
     if (threadIdx.x == 0) p.topk_count[item] = want;
 }
 
-extern "C" int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *a, void *stream)
+// ---- select, up to 8192 pages: bucket search, then (optionally) block recycling in the same launch --------------
+constexpr int FC_FAST_CACHED = 8;        // keys per thread
+constexpr int FC_FAST_MAX_PAGES_256 = 256 * FC_FAST_CACHED;     // 2048 pages: 256 threads
+constexpr int FC_FAST_MAX_PAGES = 1024 * FC_FAST_CACHED;        // 8192 pages: 1024 threads
+constexpr int FC_FAST_CAP = 512;         // candidates ranked directly
+constexpr int FC_FAST_MAX_ITERS = 64;    // refinements of a crowded bin; finite scores need at most ~26 (the range shrinks ~2047x each)
+
+template <int THREADS>
+struct fc_fast_lds {
+    int hist[2 * THREADS];
+    uint32_t cand_key[FC_FAST_CAP];
+    int cand_idx[FC_FAST_CAP];
+    float red_lo[THREADS / 64], red_hi[THREADS / 64];
+    int wave_cnt[2][THREADS / 64 + 1];
+    int bb, rem, cb, cand_n, need_eq;
+    uint32_t T;
+};
+
+// Threshold key T and the number of pages equal to T that are members (lowest indices first), for the `rem` best of
+// the candidate pages (bit i of cmask = this thread's i-th page is a candidate), 1 <= rem < number of candidates.
+template <int THREADS>
+__device__ __forceinline__ void fc_bucket_threshold(const float (&sreg)[FC_FAST_CACHED], const uint32_t (&kreg)[FC_FAST_CACHED],
+                                                    int pg0, unsigned cmask, int rem, fc_fast_lds<THREADS> &L, uint32_t &T, int &need_eq)
 {
-    if (!ctx) return FC_ERR_INVALID_ARG;
+    constexpr int BINS = 2 * THREADS, WAVES = THREADS / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    for (int iter = 0; iter < FC_FAST_MAX_ITERS; ++iter) {
+        float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i)
+            if ((cmask >> i) & 1u) { lo = fminf(lo, sreg[i]); hi = fmaxf(hi, sreg[i]); }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) { lo = fminf(lo, __shfl_xor(lo, d)); hi = fmaxf(hi, __shfl_xor(hi, d)); }
+        if (lane == 0) { L.red_lo[wv] = lo; L.red_hi[wv] = hi; }
+        L.hist[tid] = 0;
+        L.hist[tid + THREADS] = 0;
+        if (tid == 0) L.cand_n = 0;
+        __syncthreads();
+        lo = L.red_lo[0];
+        hi = L.red_hi[0];
+#pragma unroll
+        for (int k = 1; k < WAVES; ++k) { lo = fminf(lo, L.red_lo[k]); hi = fmaxf(hi, L.red_hi[k]); }
+        if (!(hi > lo)) {          // the candidates left all have one score: ties, lowest indices first
+            T = fc_order_key(hi);
+            need_eq = rem;
+            return;
+        }
+        // linear bins between lo and hi, on halves so that hi - lo cannot overflow; monotone in the score
+        const float lo_h = lo * 0.5f, scale = (float)(BINS - 1) / (hi * 0.5f - lo_h);
+        int bk[FC_FAST_CACHED];
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i) {
+            int bkt = (int)((sreg[i] * 0.5f - lo_h) * scale);
+            bkt = bkt < 0 ? 0 : (bkt > BINS - 1 ? BINS - 1 : bkt);
+            bk[i] = bkt;
+            if ((cmask >> i) & 1u) atomicAdd(&L.hist[bkt], 1);
+        }
+        __syncthreads();
+        // cumulative counts from the top bin down; thread t owns bins BINS-1-2t and BINS-2-2t
+        const int c0 = L.hist[BINS - 1 - 2 * tid], c1 = L.hist[BINS - 2 - 2 * tid];
+        int x = c0 + c1;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(x, d);
+            if (lane >= d) x += y;
+        }
+        if (lane == 63) L.wave_cnt[0][wv] = x;
+        __syncthreads();
+        int incl = x;
+        for (int k = 0; k < wv; ++k) incl += L.wave_cnt[0][k];
+        const int excl = incl - (c0 + c1);
+        if (excl < rem && incl >= rem) {          // exactly one thread: its bins hold the rem-th best candidate
+            if (excl + c0 >= rem) { L.bb = BINS - 1 - 2 * tid; L.rem = rem - excl; L.cb = c0; }
+            else { L.bb = BINS - 2 - 2 * tid; L.rem = rem - excl - c0; L.cb = c1; }
+        }
+        __syncthreads();
+        const int bb = L.bb, cb = L.cb;
+        rem = L.rem;
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i)
+            if (bk[i] != bb) cmask &= ~(1u << i);
+        if (cb <= FC_FAST_CAP) {
+#pragma unroll
+            for (int i = 0; i < FC_FAST_CACHED; ++i)
+                if ((cmask >> i) & 1u) {
+                    const int pos = atomicAdd(&L.cand_n, 1);
+                    if (pos < FC_FAST_CAP) { L.cand_key[pos] = kreg[i]; L.cand_idx[pos] = pg0 + i; }
+                }
+            __syncthreads();
+            if (tid < cb) {
+                const uint32_t mk = L.cand_key[tid];
+                const int mi = L.cand_idx[tid];
+                int rank = 0, eq_before = 0;
+                for (int c = 0; c < cb; ++c) {
+                    const uint32_t k = L.cand_key[c];
+                    const bool eq_lower = k == mk && L.cand_idx[c] < mi;
+                    rank += (k > mk || eq_lower) ? 1 : 0;
+                    eq_before += eq_lower ? 1 : 0;
+                }
+                if (rank == rem - 1) { L.T = mk; L.need_eq = eq_before + 1; }
+            }
+            __syncthreads();
+            T = L.T;
+            need_eq = L.need_eq;
+            return;
+        }
+    }
+    // not reached with finite scores
+    T = 0xFFFFFFFFu;
+    need_eq = 0;
+}
+
+template <int THREADS, bool RECYCLE>
+__global__ __launch_bounds__(THREADS) void fc_select_fast_kernel(fc_rerank_params p, fc_promote_params r)
+{
+    __shared__ fc_fast_lds<THREADS> L;
+    extern __shared__ int32_t lists[];          // RECYCLE: resident list, new list, available blocks (Kmax ints each)
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int b = blockIdx.y;
+    const int h = p.heads[blockIdx.x];
+    const size_t item = (size_t)b * p.Hkv + h;
+    const bool skip = p.rerank_mask && !p.rerank_mask[b];
+    int n_old = 0, n_free = 0, n_new = 0;
+    if (RECYCLE && !skip) {
+        // the resident list is needed only after the selection: its loads are in flight during it
+        n_old = min(max(r.resident_count[item], 0), p.Kmax);
+        n_free = min(max(r.free_count[item], 0), p.Kmax);
+        const int32_t *old_g = r.resident_pages + item * (size_t)p.Kmax;
+        for (int i = tid; i < n_old; i += THREADS) lists[i] = old_g[i];
+    }
+    if (!skip) {
+        const int ctx = p.context_lens[b];
+        int n = (ctx + FC_P - 1) / FC_P;
+        n = n > p.Nmax ? p.Nmax : (n < 0 ? 0 : n);
+        int K = p.k_per_seq[b];
+        K = K < 0 ? 0 : (K > p.Kmax ? p.Kmax : K);
+        const int want = K < n ? K : n;
+        const int forced = (ctx % FC_P != 0) ? n - 1 : -1;
+        const float *score = p.scores + item * (size_t)p.Nmax;
+        int32_t *out = p.topk_pages + item * (size_t)p.Kmax;
+
+        const int per = (n + THREADS - 1) / THREADS;      // <= FC_FAST_CACHED: consecutive pages per thread
+        const int pg0 = tid * per;
+        float sreg[FC_FAST_CACHED];
+        uint32_t kreg[FC_FAST_CACHED];
+        unsigned cmask = 0;
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i) {
+            const int pg = pg0 + i;
+            const bool live = i < per && pg < n;
+            sreg[i] = live ? score[pg] : 0.f;
+            kreg[i] = !live ? 0u : (pg == forced ? 0xFFFFFFFFu : fc_order_key(sreg[i]));
+            if (live && pg != forced) cmask |= 1u << i;
+        }
+        uint32_t T = 0;       // threshold key: pages with key > T are members
+        int need_eq = n;      // how many pages with key == T are members (lowest indices first)
+        if (want < n) {
+            const int rem = want - (forced >= 0 ? 1 : 0);     // the partially filled last page takes one place
+            if (rem >= 1) {
+                fc_bucket_threshold<THREADS>(sreg, kreg, pg0, cmask, rem, L, T, need_eq);
+            } else {          // room for the forced page only (or for nothing)
+                T = 0xFFFFFFFFu;
+                need_eq = want;
+            }
+        }
+        // index-ordered compaction: exclusive prefix sums of one count per thread (threads are in page order)
+        auto scan = [&](int mine, int slot) -> int {
+            int x = mine;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(x, d);
+                if (lane >= d) x += y;
+            }
+            if (lane == 63) L.wave_cnt[slot][wv] = x;
+            __syncthreads();
+            int before = x - mine;
+            for (int w = 0; w < wv; ++w) before += L.wave_cnt[slot][w];
+            return before;
+        };
+        int n_eq = 0;
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i) n_eq += (i < per && pg0 + i < n && kreg[i] == T) ? 1 : 0;
+        int eq_rank = scan(n_eq, 0);              // ties before this thread's pages
+        bool sel[FC_FAST_CACHED];
+        int n_sel = 0;
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i) {
+            const bool live = i < per && pg0 + i < n;
+            const bool eq = live && kreg[i] == T;
+            sel[i] = (live && kreg[i] > T) || (eq && eq_rank < need_eq);
+            eq_rank += eq ? 1 : 0;
+            n_sel += sel[i] ? 1 : 0;
+        }
+        int pos = scan(n_sel, 1);                 // members before this thread's pages
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i)
+            if (sel[i]) {
+                if (pos < want) {
+                    out[pos] = pg0 + i;
+                    if (RECYCLE) lists[p.Kmax + pos] = pg0 + i;
+                }
+                ++pos;
+            }
+        for (int i = want + tid; i < p.Kmax; i += THREADS) out[i] = -1;
+        if (tid == 0) p.topk_count[item] = want;
+        n_new = want;
+    }
+    if (RECYCLE) {
+        __syncthreads();
+        fc_recycle_body<THREADS>(r, item, skip, n_old, n_new, n_free, lists, L.wave_cnt[0]);
+    }
+}
+
+// Validates, then launches the score kernel and the selection.  With `fuse` (the filled parameters of the block
+// recycling that is to follow) and shapes that allow it, selection and recycling run in one kernel and *fused is
+// set; otherwise only the selection is launched and the caller launches the recycling kernel itself.
+int fc_rerank_launch(fc_ctx *ctx, const fc_rerank_args *a, const fc_promote_params *fuse, hipStream_t s, bool *fused)
+{
+    if (fused) *fused = false;
     FC_REQUIRE(ctx, a, "fc_rerank_topk: args is NULL");
     FC_REQUIRE(ctx, a->q && a->minmax && a->context_lens && a->stable_flag && a->k_per_seq && a->topk_pages && a->topk_count,
                "fc_rerank_topk: NULL pointer among q, minmax, context_lens, stable_flag, k_per_seq, topk_pages, topk_count");
@@ -349,11 +575,31 @@ extern "C" int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *a, void *stream
     p.topk_count = a->topk_count;
     if (p.n_stable == 0) return FC_OK;
 
-    hipStream_t s = (hipStream_t)stream;
     dim3 g1((p.Nmax + FC_SCORE_PAGES_PER_BLOCK - 1) / FC_SCORE_PAGES_PER_BLOCK, p.n_stable, p.batch);
     hipLaunchKernelGGL(fc_score_kernel, g1, dim3(256), 0, s, p);
     dim3 g2(p.n_stable, p.batch);
-    hipLaunchKernelGGL(fc_select_kernel, g2, dim3(FC_SELECT_THREADS), 0, s, p);
+    if (p.Nmax <= FC_FAST_MAX_PAGES) {
+        const size_t list_bytes = 3 * (size_t)p.Kmax * sizeof(int32_t);
+        const bool fuse_now = fuse && list_bytes <= FC_RECYCLE_MAX_LDS;
+        fc_promote_params r;
+        if (fuse_now) r = *fuse; else memset(&r, 0, sizeof r);
+        if (p.Nmax <= FC_FAST_MAX_PAGES_256) {
+            if (fuse_now) hipLaunchKernelGGL((fc_select_fast_kernel<256, true>), g2, dim3(256), list_bytes, s, p, r);
+            else hipLaunchKernelGGL((fc_select_fast_kernel<256, false>), g2, dim3(256), 0, s, p, r);
+        } else {
+            if (fuse_now) hipLaunchKernelGGL((fc_select_fast_kernel<1024, true>), g2, dim3(1024), list_bytes, s, p, r);
+            else hipLaunchKernelGGL((fc_select_fast_kernel<1024, false>), g2, dim3(1024), 0, s, p, r);
+        }
+        if (fused) *fused = fuse_now;
+    } else {
+        hipLaunchKernelGGL(fc_select_kernel, g2, dim3(FC_SELECT_THREADS), 0, s, p);
+    }
     FC_HIP(ctx, hipGetLastError());
     return FC_OK;
+}
+
+extern "C" int fc_rerank_topk(fc_ctx *ctx, const fc_rerank_args *a, void *stream)
+{
+    if (!ctx) return FC_ERR_INVALID_ARG;
+    return fc_rerank_launch(ctx, a, nullptr, (hipStream_t)stream, nullptr);
 }

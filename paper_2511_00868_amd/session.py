@@ -113,6 +113,7 @@ class DecodeSession:
         self.overlap = "ride" if cfg.pages_attended() * 8192 >= (64 << 20) else False
         if self.overlap == "ride" and promote_mode != binding.FC_PROMOTE_GATHER:
             self.overlap = "inline"        # per-page hipMemcpyAsync cannot ride in a kernel launch
+        self.fused_rerank = True   # rerank + promote through fc_rerank_promote (one call) instead of the two calls
         self.events = None     # optional dict of torch events a benchmark wants recorded on a rerank step
         self.stable = list(cfg.stable)
         for b in range(B):
@@ -218,6 +219,20 @@ class DecodeSession:
                                   promoted_count=self.promoted_count, promoted_flags=self.promoted_flags,
                                   total_promoted=self.total_promoted)
 
+    def rerank_promote(self, rerank_mask=None, copy_stream=None, mode=None):
+        """fc_rerank_topk + fc_promote_pages as the one call fc_rerank_promote."""
+        self.ctx.fc_rerank_promote(q=self.q, minmax=self.minmax, context_lens=self.context_lens, stable_flag=self.stable,
+                                   k_per_seq=self.k_per_seq, batch=self.cfg.batch, topk_pages=self.topk_pages,
+                                   topk_count=self.topk_count, resident_pages=self.resident_pages,
+                                   resident_count=self.resident_count, block_table=self.block_table,
+                                   host_block_table=self.host_block_table, free_blocks=self.free_blocks,
+                                   free_count=self.free_count, kv_pool=self.kv_pool, num_pool_blocks=self.num_pool_blocks,
+                                   host_pool=self.host_pool, num_host_blocks=self.num_host_blocks, main_stream=self.main,
+                                   side_stream=copy_stream or self.copy,
+                                   mode=self.promote_mode if mode is None else mode, rerank_mask=rerank_mask,
+                                   scores_out=self.scores, promoted_count=self.promoted_count,
+                                   promoted_flags=self.promoted_flags, total_promoted=self.total_promoted)
+
     def attend(self, head_subset: int = binding.FC_HEADS_ALL, stream=None):
         listed = [True] * len(self.stable) if self.unstable_topk else self.stable
         self.ctx.fc_sparse_decode_attn(q=self.q, kv_pool=self.kv_pool, num_pool_blocks=self.num_pool_blocks,
@@ -230,6 +245,9 @@ class DecodeSession:
     def _rerank_and_promote(self, copy, pmode):
         """Score, select, recycle and the page copies (or, with FC_PROMOTE_RIDE, only their description)."""
         ev = self.events
+        if self.fused_rerank and ev is None:
+            self.rerank_promote(copy_stream=copy, mode=pmode)
+            return
         if ev is not None:
             ev["rerank_begin"].record(self.main)
         self.rerank()

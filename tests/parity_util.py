@@ -51,13 +51,15 @@ def check_attention(out_gpu: np.ndarray, out_ref: np.ndarray, what: str) -> floa
 
 class ParityRun:
     def __init__(self, cfg: synth.DecodeConfig, *, promote_mode=binding.FC_PROMOTE_GATHER, attn_waves=0,
-                 sample_rows: Optional[int] = None, seed: int = 0, unstable_topk: bool = False, overlap="ride"):
+                 sample_rows: Optional[int] = None, seed: int = 0, unstable_topk: bool = False, overlap="ride",
+                 fused_rerank: bool = True):
         self.cfg = cfg
         self.wl = synth.Workload(cfg)
         self.sess = DecodeSession(cfg, self.wl, promote_mode=promote_mode, attn_waves=attn_waves, keep_scores=True,
                                   unstable_topk=unstable_topk)
         self.unstable_topk = unstable_topk
         self.sess.overlap = overlap
+        self.sess.fused_rerank = fused_rerank       # fc_rerank_promote, or fc_rerank_topk + fc_promote_pages
         self.dec = oracle.OracleDecoder(cfg.batch, cfg.num_q_heads, cfg.num_kv_heads, cfg.ctx, cfg.stable,
                                         cfg.topk, cfg.rerank_interval, unstable_topk=unstable_topk)
         self.mm = [oracle.seq_build_minmax(self.wl.k[b], cfg.ctx[b]) for b in range(cfg.batch)]

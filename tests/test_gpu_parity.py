@@ -41,6 +41,24 @@ def test_config5_reduced_planted_promotions():
     assert r.promoted_total > 3 * 5 * 32   # more than the cold fill: planted pages forced promotions
 
 
+@pytest.mark.parametrize("index,kw", [(2, dict(batch=3, ctx=4096 + 7, steps=6)), (3, dict(batch=2, ctx=16384, steps=17)),
+                                      (4, dict(batch=9, ctx=6000, steps=5)), (5, dict(batch=3, ctx=8192, steps=9))])
+def test_reduced_configs_through_the_two_separate_calls(index, kw):
+    """fc_rerank_topk followed by fc_promote_pages (the default everywhere else is the one call fc_rerank_promote,
+    which selects and recycles in one kernel): same oracle, same checks."""
+    _run(synth.make_config(index, **kw), fused_rerank=False)
+
+
+def test_budget_too_large_for_the_fused_kernel():
+    """K = 5000 pages: the lists of a head do not fit the LDS the fused select-and-recycle kernel may use, so
+    fc_rerank_promote runs the selection and the recycling kernel that keeps its lists in global memory."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.make_config(1, ctx=100000 + 5, steps=3), topk=(5000,), hot_per_head=40,
+                              name="budget_5000")
+    _run(cfg)
+    _run(cfg, fused_rerank=False)
+
+
 @pytest.mark.parametrize("ctx,K", [(1, 1), (15, 1), (16, 1), (17, 2), (33, 1), (100, 64), (1000, 5)])
 def test_edge_context_lengths_and_budgets(ctx, K):
     import dataclasses
@@ -259,4 +277,5 @@ def test_random_small_configurations(seed):
     print(cfg, flush=True)
     _run(cfg, attn_waves=int(rng.choice([0, 4, 16, 64])),
          promote_mode=int(rng.choice([binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_GATHER, binding.FC_PROMOTE_MEMCPY])),
-         overlap=[True, "heads", False, "inline", "heads-inline", "ride", "heads-ride"][int(rng.integers(0, 7))], unstable_topk=bool(rng.integers(0, 4) == 0))
+         overlap=[True, "heads", False, "inline", "heads-inline", "ride", "heads-ride"][int(rng.integers(0, 7))], unstable_topk=bool(rng.integers(0, 4) == 0),
+         fused_rerank=bool(seed % 3))
