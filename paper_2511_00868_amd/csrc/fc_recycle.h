@@ -98,78 +98,125 @@ __device__ __forceinline__ void fc_recycle_body(const fc_promote_params &p, size
 
     for (int i = tid; i < n_free; i += THREADS) avail[i] = fb[i];
 
-    // 1. evicted pages hand their blocks to the tail of the available list; their table entries become the null block
-    int pool = n_free;
-    for (int base = 0; base < n_old; base += THREADS) {
-        const int i = base + tid;
-        int page = -1;
-        bool ev = false;
-        if (i < n_old) {
-            page = old_l[i];
-            ev = page >= 0 && page < p.Nmax && !fc_sorted_contains(new_l, n_new, page);
+    int pool = n_free, n_prom = 0, taken = 0;
+    if (n_old <= THREADS && n_new <= THREADS) {
+        // The usual case, one list entry per thread: the table entries of the evicted pages, the host-table entries of
+        // the promoted pages and the atomic that reserves the copy-list range are all issued before any of them is
+        // waited for, so the whole step is one memory round trip deep.
+        int page_o = -1, page_n = -1;
+        bool ev = false, pr = false;
+        if (tid < n_old) {
+            page_o = old_l[tid];
+            ev = page_o >= 0 && page_o < p.Nmax && !fc_sorted_contains(new_l, n_new, page_o);
         }
-        const int32_t blk = ev ? tbl[page] : 0;
-        int tot;
-        const int r = fc_block_rank<THREADS>(ev, wave_cnt, tot);
+        if (tid < n_new) {
+            page_n = new_l[tid];
+            pr = page_n >= 0 && page_n < p.Nmax && !fc_sorted_contains(old_l, n_old, page_n);
+        }
+        const int32_t blk_o = ev ? tbl[page_o] : 0;
+        long long hb = pr ? htbl[page_n] : 0;
+        int n_ev;
+        const int r_ev = fc_block_rank<THREADS>(ev, wave_cnt, n_ev);
+        const int r_pr = fc_block_rank<THREADS>(pr, wave_cnt, n_prom);
+        if (tid == 0) wave_cnt[THREADS / 64] = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
         if (ev) {
-            if (pool + r < p.Kmax) avail[pool + r] = blk; else err |= FC_DEV_ERR_FREE_OVERFLOW;
-            tbl[page] = 0;
+            if (pool + r_ev < p.Kmax) avail[pool + r_ev] = blk_o; else err |= FC_DEV_ERR_FREE_OVERFLOW;
+            tbl[page_o] = 0;
         }
-        pool += tot;
-    }
-    if (pool > p.Kmax) pool = p.Kmax;
-
-    // 2. promoted pages: their count reserves a range of the global copy list
-    int n_prom = 0;
-    for (int base = 0; base < n_new; base += THREADS) {
-        const int i = base + tid;
-        bool pr = false;
-        if (i < n_new) {
-            const int page = new_l[i];
-            pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
-        }
-        n_prom += __syncthreads_count(pr);
-    }
-    if (tid == 0) wave_cnt[THREADS / 64] = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
-    __syncthreads();      // also makes every avail[] entry of step 1 visible
-    const int list_base = wave_cnt[THREADS / 64];
-
-    // 3. promoted pages, in ascending page order, take blocks from the front of the available list
-    int taken = 0;
-    for (int base = 0; base < n_new; base += THREADS) {
-        const int i = base + tid;
-        int page = -1;
-        bool pr = false;
-        if (i < n_new) {
-            page = new_l[i];
-            pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
-        }
-        long long hb = pr ? htbl[page] : 0;
-        int tot;
-        const int r = taken + fc_block_rank<THREADS>(pr, wave_cnt, tot);
-        if (p.promoted_flags && i < n_new) p.promoted_flags[item * (size_t)p.Kmax + i] = pr ? 1 : 0;
+        pool = min(pool + n_ev, p.Kmax);
+        __syncthreads();
+        const int list_base = wave_cnt[THREADS / 64];
+        if (p.promoted_flags && tid < n_new) p.promoted_flags[item * (size_t)p.Kmax + tid] = pr ? 1 : 0;
         if (pr) {
             long long blk = 0;
-            if (r < pool) {
-                blk = avail[r];
+            if (r_pr < pool) {
+                blk = avail[r_pr];
                 if (blk < 1 || blk >= p.num_pool_blocks || hb < 0 || hb >= p.num_host_blocks) {
                     err |= FC_DEV_ERR_CLAMPED;     // never copy to or from outside the pools
                     blk = 0;
                     hb = 0;
                 }
-                tbl[page] = (int32_t)blk;
+                tbl[page_n] = (int32_t)blk;
             } else {
                 err |= FC_DEV_ERR_NO_BLOCK;        // keep the list well formed: a no-op pair
                 hb = 0;
             }
-            if (list_base + r < p.list_capacity) {
-                p.copy_list[2 * (size_t)(list_base + r) + 0] = (int32_t)hb;
-                p.copy_list[2 * (size_t)(list_base + r) + 1] = (int32_t)blk;
+            if (list_base + r_pr < p.list_capacity) {
+                p.copy_list[2 * (size_t)(list_base + r_pr) + 0] = (int32_t)hb;
+                p.copy_list[2 * (size_t)(list_base + r_pr) + 1] = (int32_t)blk;
             }
         }
-        taken += tot;
-    }
+        taken = n_prom;
+    } else {
+        // 1. evicted pages hand their blocks to the tail of the available list; their table entries become the null block
+        for (int base = 0; base < n_old; base += THREADS) {
+            const int i = base + tid;
+            int page = -1;
+            bool ev = false;
+            if (i < n_old) {
+                page = old_l[i];
+                ev = page >= 0 && page < p.Nmax && !fc_sorted_contains(new_l, n_new, page);
+            }
+            const int32_t blk = ev ? tbl[page] : 0;
+            int tot;
+            const int r = fc_block_rank<THREADS>(ev, wave_cnt, tot);
+            if (ev) {
+                if (pool + r < p.Kmax) avail[pool + r] = blk; else err |= FC_DEV_ERR_FREE_OVERFLOW;
+                tbl[page] = 0;
+            }
+            pool += tot;
+        }
+        if (pool > p.Kmax) pool = p.Kmax;
 
+        // 2. promoted pages: their count reserves a range of the global copy list
+        for (int base = 0; base < n_new; base += THREADS) {
+            const int i = base + tid;
+            bool pr = false;
+            if (i < n_new) {
+                const int page = new_l[i];
+                pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
+            }
+            n_prom += __syncthreads_count(pr);
+        }
+        if (tid == 0) wave_cnt[THREADS / 64] = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
+        __syncthreads();      // also makes every avail[] entry of step 1 visible
+        const int list_base = wave_cnt[THREADS / 64];
+
+        // 3. promoted pages, in ascending page order, take blocks from the front of the available list
+        for (int base = 0; base < n_new; base += THREADS) {
+            const int i = base + tid;
+            int page = -1;
+            bool pr = false;
+            if (i < n_new) {
+                page = new_l[i];
+                pr = page >= 0 && page < p.Nmax && !fc_sorted_contains(old_l, n_old, page);
+            }
+            long long hb = pr ? htbl[page] : 0;
+            int tot;
+            const int r = taken + fc_block_rank<THREADS>(pr, wave_cnt, tot);
+            if (p.promoted_flags && i < n_new) p.promoted_flags[item * (size_t)p.Kmax + i] = pr ? 1 : 0;
+            if (pr) {
+                long long blk = 0;
+                if (r < pool) {
+                    blk = avail[r];
+                    if (blk < 1 || blk >= p.num_pool_blocks || hb < 0 || hb >= p.num_host_blocks) {
+                        err |= FC_DEV_ERR_CLAMPED;     // never copy to or from outside the pools
+                        blk = 0;
+                        hb = 0;
+                    }
+                    tbl[page] = (int32_t)blk;
+                } else {
+                    err |= FC_DEV_ERR_NO_BLOCK;        // keep the list well formed: a no-op pair
+                    hb = 0;
+                }
+                if (list_base + r < p.list_capacity) {
+                    p.copy_list[2 * (size_t)(list_base + r) + 0] = (int32_t)hb;
+                    p.copy_list[2 * (size_t)(list_base + r) + 1] = (int32_t)blk;
+                }
+            }
+            taken += tot;
+        }
+    }
     // 4. what is left of the available list is the new free list
     const int used = min(taken, pool);
     const int left = pool - used;

@@ -21,13 +21,17 @@
 // candidates in that bin are ranked against each other directly; a crowded bin (outliers, long runs of ties) is
 // refined the same way, and a bin of equal scores ends the search (ties to the lower index).  The same kernel can
 // go on to recycle the head's blocks (fc_rerank_promote; the fused kernel of Sec. 3.4).
+#include "fc_internal.h"
 #include "fc_recycle.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(8 * sizeof(short)))) short short8_t;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
 
-constexpr int FC_SCORE_TILES_PER_WAVE = 4;                 // 16-page tiles per wavefront, all in flight at once
+// 16-page tiles per wavefront, all in flight at once.  Measured on the 128k-context benchmark (100.7 MB of MinMax rows):
+// 1 tile 18.1 us, 2 tiles 18.5, 4 tiles 20.2 (198 VGPRs, two workgroups per CU); 4 tiles of which 2 in flight 18.9.
+// More, smaller workgroups fill and drain the chip faster, and that is what a kernel this short is made of.
+constexpr int FC_SCORE_TILES_PER_WAVE = 1;
 constexpr int FC_SCORE_PAGES_PER_BLOCK = 4 * FC_SCORE_TILES_PER_WAVE * 16;
 
 struct fc_rerank_params {
@@ -45,13 +49,13 @@ struct fc_rerank_params {
 
 struct fc_mm_regs { bf16x8_t a[8]; };
 
-// MinMax rows are read once per rerank and not again before they have left every cache: non-temporal loads.
+// Plain loads: the non-temporal hint that helps the attention kernel costs 1.5-3 us here (measured with 1, 2 and 4 tiles).
 __device__ __forceinline__ void fc_load_mm_tile(fc_mm_regs &r, const char *rows, int page, int last_page, int j)
 {
     const int pg = page > last_page ? last_page : page;
     const char *src = rows + (size_t)pg * FC_MM_ROW_BYTES + j * 16;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) r.a[s] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8_t *>(src + s * 64));
+    for (int s = 0; s < 8; ++s) r.a[s] = *reinterpret_cast<const bf16x8_t *>(src + s * 64);
 }
 
 __global__ __launch_bounds__(256) void fc_score_kernel(fc_rerank_params p)
@@ -71,8 +75,8 @@ __global__ __launch_bounds__(256) void fc_score_kernel(fc_rerank_params p)
     float *score = p.scores + item * (size_t)p.Nmax;
     const int last_page = n_pages - 1;
 
-    // every load of this wavefront's pages (32 KiB) is issued before anything waits on one: the kernel is one
-    // memory round trip deep after the context length
+    // every load of this wavefront's pages is issued before anything waits on one: the kernel is one memory round
+    // trip deep after the context length
     fc_mm_regs buf[FC_SCORE_TILES_PER_WAVE];
 #pragma unroll
     for (int t = 0; t < FC_SCORE_TILES_PER_WAVE; ++t)
@@ -331,11 +335,51 @@ __global__ __launch_bounds__(FC_SELECT_THREADS) void fc_select_kernel(fc_rerank_
 }
 
 // ---- select, up to 8192 pages: bucket search, then (optionally) block recycling in the same launch --------------
-constexpr int FC_FAST_CACHED = 8;        // keys per thread
+//
+// Threads own consecutive pages (`per` <= 8 each), so thread order is page order and one workgroup-wide prefix sum of
+// per-thread counts turns membership flags into ascending list positions.  The same holds for the two sets block
+// recycling needs (Sec. 3.4): with the resident list as a bitmap in LDS, "evicted" = resident and not selected and
+// "promoted" = selected and not resident are per-page flags of the owning thread, and their ranks in ascending page
+// order come out of the same prefix sum as the list positions: no searches, no second pass over lists.  Everything a
+// thread may need from memory for its pages (score, block-table entry, host-table entry) has an address that is
+// known at launch, so all of it is requested at once and the kernel is one memory round trip deep up to the atomic
+// that reserves the head's range of the copy list.
+constexpr int FC_FAST_CACHED = 8;        // pages per thread
 constexpr int FC_FAST_MAX_PAGES_256 = 256 * FC_FAST_CACHED;     // 2048 pages: 256 threads
 constexpr int FC_FAST_MAX_PAGES = 1024 * FC_FAST_CACHED;        // 8192 pages: 1024 threads
 constexpr int FC_FAST_CAP = 512;         // candidates ranked directly
 constexpr int FC_FAST_MAX_ITERS = 64;    // refinements of a crowded bin; finite scores need at most ~26 (the range shrinks ~2047x each)
+
+// Wavefront-wide primitives on the vector ALU's lane-shuffling operand modes (DPP): shifts inside rows of 16 lanes,
+// then "lane 15 of a row to the next row" and "lane 31 to rows 2 and 3".  A few cycles per step instead of a trip
+// through the LDS crossbar.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int fc_dpp(int old, int src) { return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xf, false); }
+
+__device__ __forceinline__ int fc_wave_scan_add(int x)      // inclusive prefix sum over the 64 lanes
+{
+    x += fc_dpp<0x111, 0xf>(0, x);      // row_shr:1 (a lane without a source keeps `old` = 0)
+    x += fc_dpp<0x112, 0xf>(0, x);
+    x += fc_dpp<0x114, 0xf>(0, x);
+    x += fc_dpp<0x118, 0xf>(0, x);
+    x += fc_dpp<0x142, 0xa>(0, x);      // row_bcast:15 into rows 1 and 3
+    x += fc_dpp<0x143, 0xc>(0, x);      // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+template <bool IS_MAX>
+__device__ __forceinline__ float fc_wave_minmax(float x)    // minimum or maximum over the 64 lanes, in every lane
+{
+    auto op = [](float a, float b) { return IS_MAX ? fmaxf(a, b) : fminf(a, b); };
+    // idempotent operation: a lane without a source combines with itself (`old` = its own value)
+    x = op(x, __int_as_float(fc_dpp<0x111, 0xf>(__float_as_int(x), __float_as_int(x))));
+    x = op(x, __int_as_float(fc_dpp<0x112, 0xf>(__float_as_int(x), __float_as_int(x))));
+    x = op(x, __int_as_float(fc_dpp<0x114, 0xf>(__float_as_int(x), __float_as_int(x))));
+    x = op(x, __int_as_float(fc_dpp<0x118, 0xf>(__float_as_int(x), __float_as_int(x))));
+    x = op(x, __int_as_float(fc_dpp<0x142, 0xa>(__float_as_int(x), __float_as_int(x))));
+    x = op(x, __int_as_float(fc_dpp<0x143, 0xc>(__float_as_int(x), __float_as_int(x))));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
 
 template <int THREADS>
 struct fc_fast_lds {
@@ -343,26 +387,52 @@ struct fc_fast_lds {
     uint32_t cand_key[FC_FAST_CAP];
     int cand_idx[FC_FAST_CAP];
     float red_lo[THREADS / 64], red_hi[THREADS / 64];
-    int wave_cnt[2][THREADS / 64 + 1];
-    int bb, rem, cb, cand_n, need_eq;
+    int wave_a[THREADS / 64], wave_b[THREADS / 64];
+    uint32_t resident_bits[FC_FAST_MAX_PAGES / 32];
+    int bb, rem, cb, cand_n, need_eq, all_eq, list_base;
     uint32_t T;
 };
 
+// Exclusive prefix sums over the workgroup of two per-thread counts packed as a = lo | hi << 16 (each sum < 65536) and
+// b; `tot_a` / `tot_b` get the workgroup sums.  One barrier; the caller separates two calls by another barrier.
+template <int THREADS>
+__device__ __forceinline__ void fc_block_scan2(int a, int b, fc_fast_lds<THREADS> &L, int &ex_a, int &ex_b, int &tot_a, int &tot_b)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int ia = fc_wave_scan_add(a), ib = fc_wave_scan_add(b);
+    if (lane == 63) { L.wave_a[wv] = ia; L.wave_b[wv] = ib; }
+    __syncthreads();
+    ex_a = ia - a;
+    ex_b = ib - b;
+    tot_a = 0;
+    tot_b = 0;
+#pragma unroll
+    for (int k = 0; k < THREADS / 64; ++k) {
+        const int ca = L.wave_a[k], cb = L.wave_b[k];
+        if (k < wv) { ex_a += ca; ex_b += cb; }
+        tot_a += ca;
+        tot_b += cb;
+    }
+}
+
 // Threshold key T and the number of pages equal to T that are members (lowest indices first), for the `rem` best of
 // the candidate pages (bit i of cmask = this thread's i-th page is a candidate), 1 <= rem < number of candidates.
+// *all_eq: every page whose key equals T is a member (the usual case: no tie is split at the boundary).
 template <int THREADS>
 __device__ __forceinline__ void fc_bucket_threshold(const float (&sreg)[FC_FAST_CACHED], const uint32_t (&kreg)[FC_FAST_CACHED],
-                                                    int pg0, unsigned cmask, int rem, fc_fast_lds<THREADS> &L, uint32_t &T, int &need_eq)
+                                                    int pg0, unsigned cmask, int rem, fc_fast_lds<THREADS> &L, uint32_t &T,
+                                                    int &need_eq, bool &all_eq)
 {
     constexpr int BINS = 2 * THREADS, WAVES = THREADS / 64;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    all_eq = false;
     for (int iter = 0; iter < FC_FAST_MAX_ITERS; ++iter) {
         float lo = INFINITY, hi = -INFINITY;
 #pragma unroll
         for (int i = 0; i < FC_FAST_CACHED; ++i)
             if ((cmask >> i) & 1u) { lo = fminf(lo, sreg[i]); hi = fmaxf(hi, sreg[i]); }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) { lo = fminf(lo, __shfl_xor(lo, d)); hi = fmaxf(hi, __shfl_xor(hi, d)); }
+        lo = fc_wave_minmax<false>(lo);
+        hi = fc_wave_minmax<true>(hi);
         if (lane == 0) { L.red_lo[wv] = lo; L.red_hi[wv] = hi; }
         L.hist[tid] = 0;
         L.hist[tid + THREADS] = 0;
@@ -390,16 +460,13 @@ __device__ __forceinline__ void fc_bucket_threshold(const float (&sreg)[FC_FAST_
         __syncthreads();
         // cumulative counts from the top bin down; thread t owns bins BINS-1-2t and BINS-2-2t
         const int c0 = L.hist[BINS - 1 - 2 * tid], c1 = L.hist[BINS - 2 - 2 * tid];
-        int x = c0 + c1;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(x, d);
-            if (lane >= d) x += y;
-        }
-        if (lane == 63) L.wave_cnt[0][wv] = x;
+        const int x = fc_wave_scan_add(c0 + c1);
+        if (lane == 63) L.wave_a[wv] = x;
         __syncthreads();
         int incl = x;
-        for (int k = 0; k < wv; ++k) incl += L.wave_cnt[0][k];
+#pragma unroll
+        for (int k = 0; k < WAVES; ++k)
+            if (k < wv) incl += L.wave_a[k];
         const int excl = incl - (c0 + c1);
         if (excl < rem && incl >= rem) {          // exactly one thread: its bins hold the rem-th best candidate
             if (excl + c0 >= rem) { L.bb = BINS - 1 - 2 * tid; L.rem = rem - excl; L.cb = c0; }
@@ -419,21 +486,39 @@ __device__ __forceinline__ void fc_bucket_threshold(const float (&sreg)[FC_FAST_
                     if (pos < FC_FAST_CAP) { L.cand_key[pos] = kreg[i]; L.cand_idx[pos] = pg0 + i; }
                 }
             __syncthreads();
-            if (tid < cb) {
+            if (cb <= 64) {
+                // the usual case: one candidate per lane of the first wavefront, the others read lane by lane
+                if (wv == 0) {
+                    const uint32_t mk = lane < cb ? L.cand_key[lane] : 0u;
+                    const int mi = lane < cb ? L.cand_idx[lane] : 0;
+                    int rank = 0, eq_before = 0, eq_all = 0;
+                    for (int c = 0; c < cb; ++c) {
+                        const uint32_t k = (uint32_t)__builtin_amdgcn_readlane((int)mk, c);
+                        const int ix = __builtin_amdgcn_readlane(mi, c);
+                        const bool eq = k == mk, eq_lower = eq && ix < mi;
+                        rank += (k > mk || eq_lower) ? 1 : 0;
+                        eq_before += eq_lower ? 1 : 0;
+                        eq_all += eq ? 1 : 0;
+                    }
+                    if (lane < cb && rank == rem - 1) { L.T = mk; L.need_eq = eq_before + 1; L.all_eq = eq_before + 1 == eq_all; }
+                }
+            } else if (tid < cb) {
                 const uint32_t mk = L.cand_key[tid];
                 const int mi = L.cand_idx[tid];
-                int rank = 0, eq_before = 0;
+                int rank = 0, eq_before = 0, eq_all = 0;
                 for (int c = 0; c < cb; ++c) {
                     const uint32_t k = L.cand_key[c];
-                    const bool eq_lower = k == mk && L.cand_idx[c] < mi;
+                    const bool eq = k == mk, eq_lower = eq && L.cand_idx[c] < mi;
                     rank += (k > mk || eq_lower) ? 1 : 0;
                     eq_before += eq_lower ? 1 : 0;
+                    eq_all += eq ? 1 : 0;
                 }
-                if (rank == rem - 1) { L.T = mk; L.need_eq = eq_before + 1; }
+                if (rank == rem - 1) { L.T = mk; L.need_eq = eq_before + 1; L.all_eq = eq_before + 1 == eq_all; }
             }
             __syncthreads();
             T = L.T;
             need_eq = L.need_eq;
+            all_eq = L.all_eq != 0;
             return;
         }
     }
@@ -446,100 +531,218 @@ template <int THREADS, bool RECYCLE>
 __global__ __launch_bounds__(THREADS) void fc_select_fast_kernel(fc_rerank_params p, fc_promote_params r)
 {
     __shared__ fc_fast_lds<THREADS> L;
-    extern __shared__ int32_t lists[];          // RECYCLE: resident list, new list, available blocks (Kmax ints each)
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    extern __shared__ int32_t avail[];          // RECYCLE: the head's available blocks (Kmax ints)
+    const int tid = threadIdx.x;
     const int b = blockIdx.y;
     const int h = p.heads[blockIdx.x];
     const size_t item = (size_t)b * p.Hkv + h;
-    const bool skip = p.rerank_mask && !p.rerank_mask[b];
-    int n_old = 0, n_free = 0, n_new = 0;
-    if (RECYCLE && !skip) {
-        // the resident list is needed only after the selection: its loads are in flight during it
-        n_old = min(max(r.resident_count[item], 0), p.Kmax);
-        n_free = min(max(r.free_count[item], 0), p.Kmax);
-        const int32_t *old_g = r.resident_pages + item * (size_t)p.Kmax;
-        for (int i = tid; i < n_old; i += THREADS) lists[i] = old_g[i];
+
+    // ---- every load whose address is known at launch, before anything waits ----------------------------------------
+    const int per = (p.Nmax + THREADS - 1) / THREADS;      // <= FC_FAST_CACHED consecutive pages per thread
+    const int pg0 = tid * per;
+    const float *score = p.scores + item * (size_t)p.Nmax;
+    int32_t *tbl = RECYCLE ? r.block_table + item * (size_t)p.Nmax : nullptr;
+    const int32_t *htbl = RECYCLE ? r.host_block_table + item * (size_t)p.Nmax : nullptr;
+    float sreg[FC_FAST_CACHED];
+    int32_t treg[FC_FAST_CACHED], hreg[FC_FAST_CACHED];
+    // eight consecutive 4-byte values of this thread: two 16-byte loads where the row allows it
+    auto load8 = [&](const int32_t *row, int32_t (&dst)[FC_FAST_CACHED]) {
+        if (per == FC_FAST_CACHED && pg0 + FC_FAST_CACHED <= p.Nmax && (reinterpret_cast<uintptr_t>(row + pg0) & 15) == 0) {
+            const int4 lo4 = reinterpret_cast<const int4 *>(row + pg0)[0], hi4 = reinterpret_cast<const int4 *>(row + pg0)[1];
+            dst[0] = lo4.x; dst[1] = lo4.y; dst[2] = lo4.z; dst[3] = lo4.w;
+            dst[4] = hi4.x; dst[5] = hi4.y; dst[6] = hi4.z; dst[7] = hi4.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < FC_FAST_CACHED; ++i) dst[i] = (i < per && pg0 + i < p.Nmax) ? row[pg0 + i] : 0;
+        }
+    };
+    {
+        int32_t sbits[FC_FAST_CACHED];
+        load8(reinterpret_cast<const int32_t *>(score), sbits);
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i) sreg[i] = __int_as_float(sbits[i]);
     }
+    if (RECYCLE) {
+        load8(tbl, treg);
+        load8(htbl, hreg);
+    }
+    const bool skip = p.rerank_mask && !p.rerank_mask[b];
+    int n_old = 0, n_free = 0;
+    if (RECYCLE) {
+        // the resident list becomes a bitmap over the pages; the free list is the head of the available blocks
+        for (int i = tid; i < FC_FAST_MAX_PAGES / 32; i += THREADS) L.resident_bits[i] = 0;
+        if (!skip) {
+            n_old = min(max(r.resident_count[item], 0), p.Kmax);
+            n_free = min(max(r.free_count[item], 0), p.Kmax);
+        }
+        const int32_t *fb = r.free_blocks + item * (size_t)p.Kmax;
+        for (int i = tid; i < p.Kmax; i += THREADS) avail[i] = fb[i];
+        __syncthreads();
+        const int32_t *old_g = r.resident_pages + item * (size_t)p.Kmax;
+        for (int i = tid; i < n_old; i += THREADS) {
+            const int page = old_g[i];
+            if (page >= 0 && page < p.Nmax) atomicOr(&L.resident_bits[page >> 5], 1u << (page & 31));
+        }
+    }
+    int want = 0;
+    unsigned sel = 0;          // bit i: this thread's i-th page is a member of the new set
     if (!skip) {
         const int ctx = p.context_lens[b];
         int n = (ctx + FC_P - 1) / FC_P;
         n = n > p.Nmax ? p.Nmax : (n < 0 ? 0 : n);
         int K = p.k_per_seq[b];
         K = K < 0 ? 0 : (K > p.Kmax ? p.Kmax : K);
-        const int want = K < n ? K : n;
+        want = K < n ? K : n;
         const int forced = (ctx % FC_P != 0) ? n - 1 : -1;
-        const float *score = p.scores + item * (size_t)p.Nmax;
-        int32_t *out = p.topk_pages + item * (size_t)p.Kmax;
 
-        const int per = (n + THREADS - 1) / THREADS;      // <= FC_FAST_CACHED: consecutive pages per thread
-        const int pg0 = tid * per;
-        float sreg[FC_FAST_CACHED];
         uint32_t kreg[FC_FAST_CACHED];
-        unsigned cmask = 0;
+        unsigned cmask = 0, live = 0;
 #pragma unroll
         for (int i = 0; i < FC_FAST_CACHED; ++i) {
             const int pg = pg0 + i;
-            const bool live = i < per && pg < n;
-            sreg[i] = live ? score[pg] : 0.f;
-            kreg[i] = !live ? 0u : (pg == forced ? 0xFFFFFFFFu : fc_order_key(sreg[i]));
-            if (live && pg != forced) cmask |= 1u << i;
+            const bool lv = i < per && pg < n;
+            kreg[i] = !lv ? 0u : (pg == forced ? 0xFFFFFFFFu : fc_order_key(sreg[i]));
+            if (lv) live |= 1u << i;
+            if (lv && pg != forced) cmask |= 1u << i;
         }
         uint32_t T = 0;       // threshold key: pages with key > T are members
         int need_eq = n;      // how many pages with key == T are members (lowest indices first)
+        bool all_eq = true;   // ... or simply all of them
         if (want < n) {
             const int rem = want - (forced >= 0 ? 1 : 0);     // the partially filled last page takes one place
             if (rem >= 1) {
-                fc_bucket_threshold<THREADS>(sreg, kreg, pg0, cmask, rem, L, T, need_eq);
+                fc_bucket_threshold<THREADS>(sreg, kreg, pg0, cmask, rem, L, T, need_eq, all_eq);
             } else {          // room for the forced page only (or for nothing)
                 T = 0xFFFFFFFFu;
                 need_eq = want;
+                all_eq = false;
             }
         }
-        // index-ordered compaction: exclusive prefix sums of one count per thread (threads are in page order)
-        auto scan = [&](int mine, int slot) -> int {
-            int x = mine;
+        int eq_rank = 0;
+        if (!all_eq) {        // a run of equal keys is split at the boundary: the lowest page indices are the members
+            int n_eq = 0;
 #pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int y = __shfl_up(x, d);
-                if (lane >= d) x += y;
-            }
-            if (lane == 63) L.wave_cnt[slot][wv] = x;
+            for (int i = 0; i < FC_FAST_CACHED; ++i) n_eq += (((live >> i) & 1u) && kreg[i] == T) ? 1 : 0;
+            int dummy0, dummy1, dummy2;
+            fc_block_scan2<THREADS>(n_eq, 0, L, eq_rank, dummy0, dummy1, dummy2);
             __syncthreads();
-            int before = x - mine;
-            for (int w = 0; w < wv; ++w) before += L.wave_cnt[slot][w];
-            return before;
-        };
-        int n_eq = 0;
-#pragma unroll
-        for (int i = 0; i < FC_FAST_CACHED; ++i) n_eq += (i < per && pg0 + i < n && kreg[i] == T) ? 1 : 0;
-        int eq_rank = scan(n_eq, 0);              // ties before this thread's pages
-        bool sel[FC_FAST_CACHED];
-        int n_sel = 0;
+        }
 #pragma unroll
         for (int i = 0; i < FC_FAST_CACHED; ++i) {
-            const bool live = i < per && pg0 + i < n;
-            const bool eq = live && kreg[i] == T;
-            sel[i] = (live && kreg[i] > T) || (eq && eq_rank < need_eq);
+            const bool lv = (live >> i) & 1u;
+            const bool eq = lv && kreg[i] == T;
+            if ((lv && kreg[i] > T) || (eq && (all_eq || eq_rank < need_eq))) sel |= 1u << i;
             eq_rank += eq ? 1 : 0;
-            n_sel += sel[i] ? 1 : 0;
         }
-        int pos = scan(n_sel, 1);                 // members before this thread's pages
-#pragma unroll
-        for (int i = 0; i < FC_FAST_CACHED; ++i)
-            if (sel[i]) {
-                if (pos < want) {
-                    out[pos] = pg0 + i;
-                    if (RECYCLE) lists[p.Kmax + pos] = pg0 + i;
-                }
-                ++pos;
-            }
-        for (int i = want + tid; i < p.Kmax; i += THREADS) out[i] = -1;
-        if (tid == 0) p.topk_count[item] = want;
-        n_new = want;
     }
-    if (RECYCLE) {
-        __syncthreads();
-        fc_recycle_body<THREADS>(r, item, skip, n_old, n_new, n_free, lists, L.wave_cnt[0]);
+
+    // ---- positions in the new list; with recycling, the ranks of the evicted and the promoted pages ------------------
+    unsigned old = 0;
+    if (RECYCLE && !skip) {
+        __syncthreads();      // the bitmap is complete
+#pragma unroll
+        for (int i = 0; i < FC_FAST_CACHED; ++i) {
+            const int pg = pg0 + i;
+            if (i < per && pg < p.Nmax && ((L.resident_bits[pg >> 5] >> (pg & 31)) & 1u)) old |= 1u << i;
+        }
+    }
+    const unsigned ev = old & ~sel, pr = sel & ~old;
+    int pos, r_pr, packed_tot, n_prom;
+    {
+        int ex_a;
+        fc_block_scan2<THREADS>(__popc(sel) | (__popc(ev) << 16), __popc(pr), L, ex_a, r_pr, packed_tot, n_prom);
+        pos = ex_a & 0xFFFF;
+        const int r_ev0 = ex_a >> 16;
+        int32_t *out = p.topk_pages + item * (size_t)p.Kmax;
+        if (!skip) {
+            int32_t *res = RECYCLE ? r.resident_pages + item * (size_t)p.Kmax : nullptr;
+            int q = pos;
+#pragma unroll
+            for (int i = 0; i < FC_FAST_CACHED; ++i)
+                if ((sel >> i) & 1u) {
+                    if (q < want) {
+                        out[q] = pg0 + i;
+                        if (RECYCLE) {
+                            res[q] = pg0 + i;
+                            if (r.promoted_flags) r.promoted_flags[item * (size_t)p.Kmax + q] = (pr >> i) & 1u;
+                        }
+                    }
+                    ++q;
+                }
+            for (int i = want + tid; i < p.Kmax; i += THREADS) {
+                out[i] = -1;
+                if (RECYCLE) res[i] = -1;
+            }
+            if (tid == 0) p.topk_count[item] = want;
+        }
+        if (RECYCLE) {
+            int err = 0;
+            const int n_ev = packed_tot >> 16;
+            if (tid == 0) L.list_base = n_prom > 0 ? atomicAdd(&r.counters[2 + r.parity], n_prom) : 0;
+            // evicted pages, in ascending page order, hand their blocks to the tail of the available list
+            int q = n_free + r_ev0;
+#pragma unroll
+            for (int i = 0; i < FC_FAST_CACHED; ++i)
+                if ((ev >> i) & 1u) {
+                    if (q < p.Kmax) avail[q] = treg[i]; else err |= FC_DEV_ERR_FREE_OVERFLOW;
+                    tbl[pg0 + i] = 0;
+                    ++q;
+                }
+            const int pool = min(n_free + n_ev, p.Kmax);
+            __syncthreads();
+            const int list_base = L.list_base;
+            // promoted pages, in ascending page order, take blocks from its front
+            q = r_pr;
+#pragma unroll
+            for (int i = 0; i < FC_FAST_CACHED; ++i)
+                if ((pr >> i) & 1u) {
+                    long long blk = 0, hb = hreg[i];
+                    if (q < pool) {
+                        blk = avail[q];
+                        if (blk < 1 || blk >= r.num_pool_blocks || hb < 0 || hb >= r.num_host_blocks) {
+                            err |= FC_DEV_ERR_CLAMPED;     // never copy to or from outside the pools
+                            blk = 0;
+                            hb = 0;
+                        }
+                        tbl[pg0 + i] = (int32_t)blk;
+                    } else {
+                        err |= FC_DEV_ERR_NO_BLOCK;        // keep the list well formed: a no-op pair
+                        hb = 0;
+                    }
+                    if (list_base + q < r.list_capacity) {
+                        r.copy_list[2 * (size_t)(list_base + q) + 0] = (int32_t)hb;
+                        r.copy_list[2 * (size_t)(list_base + q) + 1] = (int32_t)blk;
+                    }
+                    ++q;
+                }
+            // what is left of the available list is the new free list
+            const int used = min(n_prom, pool), left = pool - used;
+            int32_t *fb = r.free_blocks + item * (size_t)p.Kmax;
+            if (!skip) {
+                for (int i = tid; i < left; i += THREADS) fb[i] = avail[used + i];
+                if (tid == 0) {
+                    r.free_count[item] = left;
+                    r.resident_count[item] = want;
+                }
+            }
+            if (r.promoted_flags && skip)      // sequences that did not rerank promoted nothing
+                for (int i = tid; i < p.Kmax; i += THREADS) r.promoted_flags[item * (size_t)p.Kmax + i] = 0;
+            if (r.promoted_flags && !skip)
+                for (int i = want + tid; i < p.Kmax; i += THREADS) r.promoted_flags[item * (size_t)p.Kmax + i] = 0;
+            if (tid == 0 && r.promoted_count) r.promoted_count[item] = n_prom;
+            if (err) atomicOr(&r.counters[1], err);
+            if (tid == 0 && r.publish) {          // FC_PROMOTE_MEMCPY: the workgroup that finishes last publishes the pair count
+                __threadfence();
+                const int done = atomicAdd(&r.counters[4], 1);
+                if (done == (int)(gridDim.x * gridDim.y) - 1) {
+                    const int total = atomicAdd(&r.counters[2 + r.parity], 0);
+                    if (r.host_total) *r.host_total = total;
+                    if (r.host_total2) *r.host_total2 = total;
+                    r.counters[2 + (r.parity ^ 1)] = 0;
+                    r.counters[4] = 0;
+                }
+            }
+        }
     }
 }
 
@@ -579,7 +782,7 @@ int fc_rerank_launch(fc_ctx *ctx, const fc_rerank_args *a, const fc_promote_para
     hipLaunchKernelGGL(fc_score_kernel, g1, dim3(256), 0, s, p);
     dim3 g2(p.n_stable, p.batch);
     if (p.Nmax <= FC_FAST_MAX_PAGES) {
-        const size_t list_bytes = 3 * (size_t)p.Kmax * sizeof(int32_t);
+        const size_t list_bytes = (size_t)p.Kmax * sizeof(int32_t);      // the head's available blocks
         const bool fuse_now = fuse && list_bytes <= FC_RECYCLE_MAX_LDS;
         fc_promote_params r;
         if (fuse_now) r = *fuse; else memset(&r, 0, sizeof r);
