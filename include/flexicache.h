@@ -272,8 +272,14 @@ const char *fc_static_last_error(void);
  *     host_pool[host_block_table[b][h][page]] (Sec. 3.3 "Minimizing Transfer Size"); it stays resident
  *     until a later rerank evicts it.
  * Afterwards context_lens[b] += 1.  Needs: page < Nmax, a free block when a page starts, room in the
- * resident list (Kmax > budget + pages started between two reranks); violations set the device error
- * word (fc_check_device_state) and leave that head's state untouched. */
+ * resident list (Kmax > budget + pages started between two reranks).  Violations set the device error
+ * word (fc_check_device_state).  A head that cannot take its token (no room in the tables, no free
+ * block) writes nothing, and the length of its sequence is then NOT advanced, so that no head is left
+ * with a token position that has no block behind it; the other heads of that sequence have written the
+ * token all the same, so after FC_ERR_STATE the caller has to drop or rebuild that sequence.
+ * Page copies that an earlier fc_promote_pages left in flight (or, with FC_PROMOTE_RIDE, not yet
+ * launched) are ordered before this call's writes to the pool, as for an attention call; the same holds
+ * for fc_offload_pages. */
 typedef struct {
     const void *k_new;               /* dev bf16 [batch][num_kv_heads][D] */
     const void *v_new;               /* dev bf16 [batch][num_kv_heads][D] */
@@ -328,7 +334,9 @@ int fc_classify_heads(fc_ctx *ctx, const int32_t *bottom_counts, int32_t heads, 
                       uint8_t *unstable_out, void *stream);
 
 /* Reads (and clears) the device-side error word set by the bookkeeping kernels (a head owning too
- * few blocks, an id out of range that was clamped).  Synchronises `stream`.  Returns FC_OK or
+ * few blocks, an id out of range that was clamped) and by the attention kernel (a list or table entry
+ * outside its range, which it clamps so that every access stays in bounds, or an attended page whose
+ * table entry is the null block).  Synchronises `stream`.  Returns FC_OK or
  * FC_ERR_STATE. */
 int fc_check_device_state(fc_ctx *ctx, void *stream);
 

@@ -24,6 +24,7 @@ struct fc_append_params {
     unsigned long long stable_mask;
     int batch, Hkv, Nmax, Kmax;
     int32_t *counters;           // [1] = error bits, [5] = workgroups done
+    int32_t *seq_flags;          // [batch]: set when a head of the sequence could not take its token; cleared by the last workgroup
 };
 
 __global__ __launch_bounds__(128) void fc_append_kernel(fc_append_params p)
@@ -33,12 +34,14 @@ __global__ __launch_bounds__(128) void fc_append_kernel(fc_append_params p)
     const size_t item = (size_t)b * p.Hkv + h;
     const bool active = !p.append_mask || p.append_mask[b];
     int err = 0;
+    bool failed = false;      // this head could not take the token (no room in the tables, no block)
     if (active) {
         const int pos = p.context_lens[b];
         const int page = pos >> 4, slot = pos & 15;
         const bool stable = (p.stable_mask >> h) & 1ull;
         if (pos < 0 || page >= p.Nmax) {
             err = FC_DEV_ERR_CLAMPED;              // no room in the tables: nothing is written
+            failed = true;
         } else {
             int32_t *tbl = p.block_table + item * (size_t)p.Nmax;
             if (d == 0) {
@@ -69,6 +72,7 @@ __global__ __launch_bounds__(128) void fc_append_kernel(fc_append_params p)
             }
             __syncthreads();
             const long long blk = sh_blk;
+            failed = blk <= 0;
             if (blk > 0) {
                 uint16_t *pg = p.pool + (size_t)blk * FC_PAGE_ELEMS;
                 const uint16_t kx = p.k_new[item * FC_D + d], vx = p.v_new[item * FC_D + d];
@@ -98,7 +102,8 @@ __global__ __launch_bounds__(128) void fc_append_kernel(fc_append_params p)
             }
         }
     }
-    if (err) atomicOr(&p.counters[1], err);
+    if (err && d == 0) atomicOr(&p.counters[1], err);
+    if (failed && d == 0) atomicOr(&p.seq_flags[b], 1);
     // every workgroup has read the old lengths by now; the last one to finish advances them
     __syncthreads();
     if (d == 0) {
@@ -109,7 +114,10 @@ __global__ __launch_bounds__(128) void fc_append_kernel(fc_append_params p)
     if (sh_blk) {
         for (int i = d; i < p.batch; i += 128) {
             const int pos = p.context_lens[i];
-            if ((!p.append_mask || p.append_mask[i]) && pos >= 0 && (pos >> 4) < p.Nmax) p.context_lens[i] = pos + 1;
+            // a sequence one of whose heads could not take the token keeps its length: no head is left with a
+            // token position that has no block behind it
+            const int failed = atomicExch(&p.seq_flags[i], 0);
+            if ((!p.append_mask || p.append_mask[i]) && !failed && pos >= 0 && (pos >> 4) < p.Nmax) p.context_lens[i] = pos + 1;
         }
         if (d == 0) p.counters[5] = 0;
     }
@@ -165,6 +173,14 @@ extern "C" int fc_append_kv(fc_ctx *ctx, const fc_append_args *a, void *stream)
     p.Nmax = ctx->cfg.max_pages_per_seq;
     p.Kmax = ctx->cfg.max_topk;
     p.counters = fc_ws_ptr<int32_t>(ctx, ctx->lay.counters);
+    p.seq_flags = fc_ws_ptr<int32_t>(ctx, ctx->lay.seq_flags);
+    // page copies of an earlier fc_promote_pages may still be on their way into the pool (the partially filled last
+    // page of a stable head among them): they land before this call writes the pool
+    {
+        int st = fc_launch_deferred_copies(ctx, stream);
+        if (st == FC_OK) st = fc_wait_for_copies(ctx, stream);
+        if (st != FC_OK) return st;
+    }
     hipLaunchKernelGGL(fc_append_kernel, dim3(p.Hkv, p.batch), dim3(128), 0, (hipStream_t)stream, p);
     FC_HIP(ctx, hipGetLastError());
     return FC_OK;
@@ -177,6 +193,11 @@ extern "C" int fc_offload_pages(fc_ctx *ctx, const void *kv_pool, int64_t num_po
     FC_REQUIRE(ctx, kv_pool && host_pool && (pairs || n_pairs == 0), "fc_offload_pages: NULL pointer");
     FC_REQUIRE(ctx, n_pairs >= 0 && num_pool_blocks >= 2 && num_host_blocks >= 2, "fc_offload_pages: sizes out of range");
     if (n_pairs == 0) return FC_OK;
+    {   // pages being promoted into the pool land before the pool is read
+        int st = fc_launch_deferred_copies(ctx, stream);
+        if (st == FC_OK) st = fc_wait_for_copies(ctx, stream);
+        if (st != FC_OK) return st;
+    }
     const int grid = n_pairs < ctx->gather_blocks ? n_pairs : ctx->gather_blocks;
     hipLaunchKernelGGL(fc_offload_pages_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, pairs, n_pairs,
                        (const uint4 *)kv_pool, (long long)num_pool_blocks, (uint4 *)host_pool, (long long)num_host_blocks);

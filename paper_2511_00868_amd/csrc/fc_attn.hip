@@ -61,6 +61,7 @@ struct fc_attn_params {
     float *part_acc;
     float *out;
     float *lse;
+    int32_t *err;          // device error word (may be NULL): set when an id had to be clamped or an attended page is not resident
     int attn_blocks;       // workgroups 0 .. attn_blocks-1 attend; any beyond them copy promoted pages (copy_blocks of them)
     int copy_blocks;
     fc_copy_job copies;
@@ -275,18 +276,26 @@ __global__ __launch_bounds__(256, 2) void fc_decode_attn_kernel(fc_attn_params p
         for (int base = lo; base < hi; base += 64) {
             const int cnt = min(64, hi - base);
             int blk_v = 0, ntok_v = FC_P;
+            int bad = 0;
             if (lane < cnt) {
-                int logical = stable ? lst[base + lane] : base + lane;
-                logical = logical < 0 ? 0 : (logical > last_page ? last_page : logical);
-                long long blk = tbl[logical];
-                blk = blk < 0 ? 0 : (blk >= p.num_blocks ? p.num_blocks - 1 : blk);
+                const int listed = stable ? lst[base + lane] : base + lane;
+                const int logical = listed < 0 ? 0 : (listed > last_page ? last_page : listed);
+                const long long entry = tbl[logical];
+                const long long blk = entry < 0 ? 0 : (entry >= p.num_blocks ? p.num_blocks - 1 : entry);
                 blk_v = (int)blk;
                 ntok_v = logical == last_page ? last_ntok : FC_P;
                 if (p.page_filter != 0) {     // 0 valid tokens = this call leaves the page to its partner call
                     const bool fresh = stable && p.promoted_flags[(size_t)item * p.Kmax + base + lane] != 0;
                     if ((p.page_filter == 1) == fresh) ntok_v = 0;
                 }
+                // ids stay in bounds whatever the tables hold, but a clamped id or an attended page without a block
+                // (entry 0, the null block) means the caller's state is broken: say so instead of answering plausibly
+                if (ntok_v > 0) {
+                    if (listed != logical || entry != blk) bad = FC_DEV_ERR_CLAMPED;
+                    else if (blk == 0) bad = FC_DEV_ERR_NOT_RESIDENT;
+                }
             }
+            if (p.err && __any(bad != 0) && bad != 0) atomicOr(p.err, bad);
             fc_page_regs buf[FC_ATTN_NBUF];
 #pragma unroll
             for (int i = 0; i < FC_ATTN_NBUF; ++i)
@@ -519,6 +528,7 @@ extern "C" int fc_sparse_decode_attn(fc_ctx *ctx, const fc_attn_args *a, void *s
     p.part_acc = fc_ws_ptr<float>(ctx, ctx->lay.part_acc);
     p.out = a->out;
     p.lse = a->lse;
+    p.err = fc_ws_ptr<int32_t>(ctx, ctx->lay.counters) + 1;
 
     const bool first_of_pair = sub == FC_HEADS_UNSTABLE || sub == FC_PAGES_RESIDENT;
     const bool merge_now = !first_of_pair;
@@ -721,6 +731,7 @@ extern "C" int fc_sparse_decode_attn_static(const fc_config *cfg, const fc_attn_
     p.part_acc = reinterpret_cast<float *>(d.scratch + acc_off);
     p.out = a->out;
     p.lse = a->lse;
+    p.err = nullptr;       // no context, no error word: ids are clamped silently here
     p.attn_blocks = waves / 4;
     p.copy_blocks = 0;
     p.copies = fc_copy_job{};

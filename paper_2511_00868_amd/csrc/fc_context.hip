@@ -47,6 +47,7 @@ static void fc_make_layout(const fc_config &c, int attn_waves, fc_ws_layout *l)
     l->part_acc = take(2 * slots * (size_t)G * FC_D * sizeof(float));
     l->copy_list = take(items * (size_t)c.max_topk * 2 * sizeof(int32_t));
     l->counters = take(8 * sizeof(int32_t));
+    l->seq_flags = take((size_t)c.max_batch * sizeof(int32_t));
     l->total = off;
 }
 
@@ -146,8 +147,9 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
         delete c;
         return FC_ERR_HIP;
     }
-    // the counter block must start at zero
+    // the counter block and the per-sequence flags must start at zero
     if (hipMemset(c->ws + c->lay.counters, 0, 8 * sizeof(int32_t)) != hipSuccess ||
+        hipMemset(c->ws + c->lay.seq_flags, 0, (size_t)cfg->max_batch * sizeof(int32_t)) != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
         (void)hipEventDestroy(c->ev_diff_done);
         (void)hipEventDestroy(c->ev_copies_done);
@@ -209,7 +211,7 @@ extern "C" int fc_check_device_state(fc_ctx *ctx, void *stream)
         int32_t zero = 0;
         FC_HIP(ctx, hipMemcpyAsync(dev_err, &zero, sizeof zero, hipMemcpyHostToDevice, s));
         FC_HIP(ctx, hipStreamSynchronize(s));
-        return fc_fail(ctx, FC_ERR_STATE, "device error word = %d (1: head owns too few blocks, 2: id clamped, 4: free list overflow)", v);
+        return fc_fail(ctx, FC_ERR_STATE, "device error word = %d (1: head owns too few blocks, 2: id clamped, 4: free list overflow, 8: attended page not resident)", v);
     }
     return FC_OK;
 }

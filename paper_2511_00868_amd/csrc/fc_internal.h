@@ -26,6 +26,7 @@ constexpr int FC_MAX_ITEMS = 4096;                   // max_batch * num_kv_heads
 constexpr int FC_DEV_ERR_NO_BLOCK = 1;     // a head owned too few blocks for its promoted pages
 constexpr int FC_DEV_ERR_CLAMPED = 2;      // an id outside its valid range was clamped
 constexpr int FC_DEV_ERR_FREE_OVERFLOW = 4;
+constexpr int FC_DEV_ERR_NOT_RESIDENT = 8; // attention was asked to read a page whose table entry is the null block
 
 // Partition of the caller's device workspace.
 struct fc_ws_layout {
@@ -35,6 +36,7 @@ struct fc_ws_layout {
     size_t part_acc;      // float [2][slots][G][128]
     size_t copy_list;     // int32 [max_items * Kmax][2]
     size_t counters;      // int32 [8]: 1 = err, 2..3 = copy-pair counts (alternating calls), 4 = recycle workgroups done, 5 = append workgroups done
+    size_t seq_flags;     // int32 [max_batch]: fc_append_kv: a head of this sequence could not take its token (cleared by the same call)
     size_t total;
 };
 

@@ -19,7 +19,7 @@ def test_bad_arguments_are_rejected_before_anything_is_launched():
     try:
         q = torch.zeros((2, 8, 128), dtype=torch.bfloat16, device="cuda")
         out = torch.zeros((2, 8, 128), dtype=torch.float32, device="cuda")
-        tbl = torch.zeros((2, 2, 16), dtype=torch.int32, device="cuda")
+        tbl = torch.ones((2, 2, 16), dtype=torch.int32, device="cuda")       # every page in block 1
         lens = torch.ones(2, dtype=torch.int32, device="cuda")
         pool = torch.zeros((4, 4096), dtype=torch.bfloat16, device="cuda")
         ok = dict(q=q, kv_pool=pool, num_pool_blocks=4, block_table=tbl, context_lens=lens, stable_flag=[False, False],
@@ -217,9 +217,10 @@ def test_free_running_loop_without_host_synchronisation(overlap, steps):
     cfg = synth.make_config(5, batch=3, ctx=8192, steps=steps)
     cfg = dataclasses.replace(cfg, dynamics="static")       # the inputs stay put; the queries alone move the selection
     wl = synth.Workload(cfg)
-    s = DecodeSession(cfg, wl)
+    s = DecodeSession(cfg, wl, keep_scores=True)
     s.overlap = overlap
     try:
+        from parity_util import audit_sets
         T = cfg.steps
         qs = [wl.queries(t) for t in range(T)]
         q_dev = torch.stack([s.bits_to_dev(q) for q in qs])
@@ -252,14 +253,24 @@ def test_free_running_loop_without_host_synchronisation(overlap, steps):
                 if cfg.is_rerank_step(t):
                     dec.rerank(b, qs[t][b], mm[b])
                 for h in range(cfg.num_kv_heads):
-                    if cfg.stable[h]:      # the selection itself: equal up to a few near-tie swaps at the boundary
-                        diff = len(set(sel[(b, h)].tolist()) ^ set(dec.sel[(b, h)].tolist()))
-                        assert len(sel[(b, h)]) == len(dec.sel[(b, h)]) and diff <= 4
-                        swaps += diff
-                ref, _ = dec.attend(b, qs[t][b], wl.k[b], wl.v[b], override=sel)
+                    if cfg.stable[h]:
+                        # the selection itself: identical, except where the oracle's own fp64 scores show a near-tie at
+                        # the budget boundary (the rule of the parity harness; an ordering race between scoring and
+                        # selection would show up here as a swap that no near-tie explains); between reranks the
+                        # list must not move at all
+                        g, o = sel[(b, h)], dec.sel[(b, h)]
+                        assert np.all(np.diff(g) > 0)
+                        if cfg.is_rerank_step(t):
+                            audit_sets(g, o, dec.last_scores[(b, h)], -1)
+                            if set(g.tolist()) != set(o.tolist()):
+                                swaps += 1
+                                dec.sel[(b, h)] = np.array(sorted(g.tolist()), dtype=np.int32)   # follow the legal swap
+                        else:
+                            np.testing.assert_array_equal(g, o)
+                ref, _ = dec.attend(b, qs[t][b], wl.k[b], wl.v[b])
                 err = np.abs(outs[t, b] - ref).max(axis=1) / np.abs(ref).max(axis=1)
                 assert err.max() <= 2e-3, (t, b, err.max())
-        print(f"free-running {overlap}: near-tie differences {swaps}")
+        print(f"free-running {overlap}: near-tie swaps {swaps}")
     finally:
         s.close()
 
@@ -297,5 +308,74 @@ def test_riding_copies_that_no_pair_carries_are_launched_on_their_own():
                 dec.rerank(b, q[b], mm[b])
                 ref, _ = dec.attend(b, q[b], wl.k[b], wl.v[b], override=sel)
                 assert (np.abs(got[b] - ref).max(axis=1) / np.abs(ref).max(axis=1)).max() <= 2e-3
+    finally:
+        s.close()
+
+
+def test_attention_reports_broken_tables_instead_of_answering_plausibly():
+    """A block-table entry outside the pool, a list entry outside the sequence, and an attended page whose
+    table entry is the null block: the attention kernel keeps every access in bounds (so it exits normally
+    and the output is finite where the clamped block holds numbers) and sets the device error word, which
+    fc_check_device_state turns into FC_ERR_STATE."""
+    import torch
+    cfg = synth.make_config(1, ctx=1000, steps=2)
+    wl = synth.Workload(cfg)
+    s = DecodeSession(cfg, wl)
+    try:
+        s.set_queries(wl.queries(0))
+        s.step(0)
+        torch.cuda.synchronize()
+        s.ctx.fc_check_device_state()
+        good_table, good_list = s.block_table.clone(), s.resident_pages.clone()
+
+        def attend_expecting(text):
+            s.attend()
+            torch.cuda.synchronize()
+            with pytest.raises(binding.FlexiCacheError) as e:
+                s.ctx.fc_check_device_state()
+            assert e.value.status == binding.FC_ERR_STATE and text in str(e.value)
+            s.ctx.fc_check_device_state()            # cleared by the read
+            s.block_table.copy_(good_table)
+            s.resident_pages.copy_(good_list)
+
+        s.block_table[0, 1, 7] = s.num_pool_blocks + 12345       # unstable head, beyond the pool
+        attend_expecting("= 2")
+        s.block_table[0, 1, 3] = -9
+        attend_expecting("= 2")
+        s.resident_pages[0, 0, 2] = 10 ** 6                       # stable head, a page the sequence does not have
+        attend_expecting("= 2")
+        s.block_table[0, 1, 11] = 0                               # an attended page without a block
+        attend_expecting("= 8")
+        s.attend()                                                # and with the tables restored all is well again
+        torch.cuda.synchronize()
+        s.ctx.fc_check_device_state()
+        assert torch.isfinite(s.out).all()
+    finally:
+        s.close()
+
+
+def test_append_without_a_free_block_keeps_the_sequence_length():
+    """fc_append_kv at a page boundary for a head that owns no free block: the error word is set, nothing is
+    written for that head, and the sequence's length stays where it was (the other sequence advances)."""
+    import torch
+    cfg = dataclasses.replace(synth.make_config(1, ctx=2048, batch=2, steps=3), append_tokens=2, name="append_no_block")
+    wl = synth.Workload(cfg)
+    s = DecodeSession(cfg, wl)
+    try:
+        s.set_queries(wl.queries(0))
+        s.step(0)
+        torch.cuda.synchronize()
+        assert s.context_lens.cpu().tolist() == [2048, 2048]      # the next token starts page 128 in every head
+        s.free_count[0, 1] = 0                                    # sequence 0, unstable head: nothing to start it in
+        table_before = s.block_table.clone()
+        k, v = wl.append(1)
+        s.append(k, v)
+        torch.cuda.synchronize()
+        with pytest.raises(binding.FlexiCacheError) as e:
+            s.ctx.fc_check_device_state()
+        assert e.value.status == binding.FC_ERR_STATE
+        assert s.context_lens.cpu().tolist() == [2048, 2049]
+        assert torch.equal(s.block_table[0, 1], table_before[0, 1])
+        assert int(s.block_table[1, 1, 128]) > 0
     finally:
         s.close()
