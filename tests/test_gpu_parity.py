@@ -49,9 +49,10 @@ def test_reduced_configs_through_the_two_separate_calls(index, kw):
     _run(synth.make_config(index, **kw), fused_rerank=False)
 
 
-def test_budget_too_large_for_the_fused_kernel():
-    """K = 5000 pages: the lists of a head do not fit the LDS the fused select-and-recycle kernel may use, so
-    fc_rerank_promote runs the selection and the recycling kernel that keeps its lists in global memory."""
+def test_budget_of_5000_pages():
+    """K = 5000 of 6251 pages: the selection runs on 1024 threads; through the two separate calls the recycling
+    kernel cannot keep its three lists in LDS and takes the variant that works on the lists in global memory;
+    through fc_rerank_promote the one-kernel path still applies (it needs one list of K entries in LDS)."""
     import dataclasses
     cfg = dataclasses.replace(synth.make_config(1, ctx=100000 + 5, steps=3), topk=(5000,), hot_per_head=40,
                               name="budget_5000")

@@ -108,3 +108,24 @@ def test_group_maximum_and_several_heads():
         per_query = [oracle.page_scores(bf16(q[h * G + g:h * G + g + 1]), np.stack([bf16(lo[h]), bf16(hi[h])], axis=1))
                      for g in range(G)]
         np.testing.assert_array_equal(s, np.max(per_query, axis=0))
+
+
+@pytest.mark.parametrize("n,K,distinct,outlier", [(3000, 500, 400, 99840.0), (8000, 700, 512, 99840.0), (2000, 150, 200, 30000.0),
+                                                  (6000, 3000, 512, -99840.0), (1900, 37, 60, 3.0e38)])
+def test_outliers_crowd_the_scores_into_a_few_bins(n, K, distinct, outlier):
+    """Integer scores 0..distinct-1 (each shared by several pages: exact ties) plus a handful of far outliers: the
+    linear bins between minimum and maximum then hold dozens of distinct values each, so the bin with the K-th
+    largest score is crowded (ranked through LDS, or refined again when it holds more than 512 candidates), and
+    the ties inside it must still go to the lower page indices."""
+    rng = np.random.default_rng(n + K)
+    val = rng.integers(0, distinct, size=n)
+    row = np.zeros((1, n, 128), dtype=np.float32)
+    row[0, :, 0] = val % 256                     # exact in bf16
+    row[0, :, 1] = (val // 256) * 256
+    far = rng.choice(n, size=7, replace=False)
+    row[0, far, 2] = outlier
+    q = np.zeros((4, 128), dtype=np.float32)
+    q[:, :3] = 1.0
+    for ctx in (n * 16, n * 16 - 3):
+        (got, ref, s), = run_case(q, row, row, ctx, K)
+        assert len(np.unique(s)) >= min(distinct, 50)
