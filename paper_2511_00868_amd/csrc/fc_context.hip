@@ -160,7 +160,6 @@ extern "C" int fc_create(fc_ctx **out, const fc_config *cfg, void *dev_workspace
     c->copies_pending = false;
     c->diff_valid = false;
     c->pending_pair = 0;
-    c->promote_calls = 0;
     // measured on the 32k-context benchmark (us per step): gather kernel beside the attention launch 16 -> 149,
     // 32 -> 131, 64 -> 143 workgroups; riding inside the attention launch 24 -> 133, 32 -> 128.4, 40 -> 127.3,
     // 48 -> 127.3, 56 -> 129.3, 64 -> 131

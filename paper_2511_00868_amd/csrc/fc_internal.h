@@ -35,7 +35,7 @@ struct fc_ws_layout {
     size_t part_ml;       // float [2][slots][16][2]  (running max in log2 units, running sum)
     size_t part_acc;      // float [2][slots][G][128]
     size_t copy_list;     // int32 [max_items * Kmax][2]
-    size_t counters;      // int32 [8]: 1 = err, 2..3 = copy-pair counts (alternating calls), 4 = recycle workgroups done, 5 = append workgroups done
+    size_t counters;      // int32 [8]: 1 = err, 2 = copy-pair count, 4 = recycle workgroups done, 5 = append workgroups done, 6 = copier workgroups done
     size_t seq_flags;     // int32 [max_batch]: fc_append_kv: a head of this sequence could not take its token (cleared by the same call)
     size_t total;
 };
@@ -43,8 +43,8 @@ struct fc_ws_layout {
 // Page copies that fc_promote_pages left for the next attention launch (FC_PROMOTE_RIDE).
 struct fc_copy_job {
     const int32_t *copy_list;    // pairs (host block, pool block)
-    const int32_t *pair_count;   // device counter the recycle kernel appended to
-    int32_t *other_count;        // the counter the next call will use: cleared by the copier
+    int32_t *pair_count;         // device counter the recycle kernel appended to; cleared by the copier's last workgroup
+    int32_t *ticket;             // device counter of copier workgroups that are done
     int32_t *host_total;         // pinned, may be NULL: receives the pair count
     int list_capacity;
     const uint4 *host_pool;
@@ -60,10 +60,7 @@ __device__ __forceinline__ void fc_copy_pages(const fc_copy_job &c, int wg, int 
     constexpr int V = FC_PAGE_BYTES / 16;   // 512 x 16 B per page
     static_assert(V % (FC_COPY_UNROLL * FC_COPY_THREADS) == 0, "a page must be a whole number of copy rounds");
     int total = c.pair_count[0];
-    if (wg == 0 && tid == 0) {
-        if (c.host_total) *c.host_total = total;
-        *c.other_count = 0;
-    }
+    if (wg == 0 && tid == 0 && c.host_total) *c.host_total = total;
     total = total > c.list_capacity ? c.list_capacity : total;
     for (int i = wg; i < total; i += n_wg) {
         const long long src = c.copy_list[2 * (size_t)i], dst = c.copy_list[2 * (size_t)i + 1];
@@ -76,6 +73,15 @@ __device__ __forceinline__ void fc_copy_pages(const fc_copy_job &c, int wg, int 
             for (int u = 0; u < FC_COPY_UNROLL; ++u) x[u] = s[k + u * FC_COPY_THREADS];
 #pragma unroll
             for (int u = 0; u < FC_COPY_UNROLL; ++u) d[k + u * FC_COPY_THREADS] = x[u];
+        }
+    }
+    // The count has to be zero again before the next recycling kernel adds to it, and it may not change while
+    // another copying workgroup has still to read it: the workgroup that finishes last clears it (every workgroup
+    // has read it by then).  Nothing here depends on host-side state, so a captured launch can be replayed.
+    if (tid == 0) {
+        if (atomicAdd(c.ticket, 1) == n_wg - 1) {
+            *c.pair_count = 0;
+            *c.ticket = 0;
         }
     }
 }
@@ -105,7 +111,6 @@ struct fc_ctx {
     bool copies_recorded;       // ev_copies_done has been recorded behind them (not done for in-line copies until another stream asks)
     bool copies_pending;
     int pending_pair;        // FC_HEADS_UNSTABLE or FC_PAGES_RESIDENT has left partials for its partner call to merge, else 0
-    unsigned promote_calls;
     int gather_blocks;    // workgroups of the host->HBM gather kernel (few and small: see fc_promote.hip)
     int ride_blocks;      // copying workgroups added to an attention launch (FC_PROMOTE_RIDE)
     // kernel timing

@@ -111,7 +111,7 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_global_kernel(f
         fc_block_rank256(pr, wave_cnt, tot);
         n_prom += tot;
     }
-    if (tid == 0) sh_list_base = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
+    if (tid == 0) sh_list_base = n_prom > 0 ? atomicAdd(&p.counters[2], n_prom) : 0;
     __syncthreads();
     const int list_base = sh_list_base;
 
@@ -183,10 +183,10 @@ __global__ __launch_bounds__(FC_RECYCLE_THREADS) void fc_recycle_global_kernel(f
         __threadfence();
         const int done = atomicAdd(&p.counters[4], 1);
         if (done == (int)(gridDim.x * gridDim.y) - 1) {
-            const int total = atomicAdd(&p.counters[2 + p.parity], 0);
+            const int total = atomicAdd(&p.counters[2], 0);
             if (p.host_total) *p.host_total = total;
             if (p.host_total2) *p.host_total2 = total;
-            p.counters[2 + (p.parity ^ 1)] = 0;
+            p.counters[2] = 0;
             p.counters[4] = 0;
         }
     }
@@ -260,7 +260,6 @@ static int fc_promote_impl(fc_ctx *ctx, const fc_promote_args *a, void *main_str
     p.num_pool_blocks = a->num_pool_blocks;
     p.num_host_blocks = a->num_host_blocks;
     p.counters = fc_ws_ptr<int32_t>(ctx, ctx->lay.counters);
-    p.parity = ctx->promote_calls & 1;
     p.publish = a->mode == FC_PROMOTE_MEMCPY;
     p.host_total = a->total_promoted;
     p.list_capacity = ctx->max_items * ctx->cfg.max_topk;
@@ -304,7 +303,6 @@ static int fc_promote_impl(fc_ctx *ctx, const fc_promote_args *a, void *main_str
         hipLaunchKernelGGL(fc_recycle_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), list_bytes, ms, p);
     else
         hipLaunchKernelGGL(fc_recycle_global_kernel, dim3(p.n_stable, p.batch), dim3(FC_RECYCLE_THREADS), 0, ms, p);
-    ++ctx->promote_calls;
     FC_HIP(ctx, hipGetLastError());
     if (a->mode == FC_PROMOTE_RIDE) {
         // single-stream mode: whatever follows on main_stream is ordered behind the recycle kernel by the stream
@@ -318,8 +316,8 @@ static int fc_promote_impl(fc_ctx *ctx, const fc_promote_args *a, void *main_str
 
     fc_copy_job job;
     job.copy_list = p.copy_list;
-    job.pair_count = p.counters + 2 + p.parity;
-    job.other_count = p.counters + 2 + (p.parity ^ 1);
+    job.pair_count = p.counters + 2;
+    job.ticket = p.counters + 6;
     job.host_total = a->total_promoted;
     job.list_capacity = p.list_capacity;
     job.host_pool = (const uint4 *)a->host_pool;

@@ -34,11 +34,10 @@ struct fc_promote_params {
     uint8_t heads[64];
     long long num_pool_blocks, num_host_blocks;
     int32_t *copy_list;     // device or pinned: pairs (host block, pool block)
-    int32_t *counters;      // device: [1] = error bits, [2 + parity] = pairs appended, [4] = workgroups done
+    int32_t *counters;      // device: [1] = error bits, [2] = pairs appended since the last copier ran, [4] = workgroups done
     int lds_lists;          // the page lists fit in dynamic LDS
-    int parity;             // calls alternate between two pair counters; each call clears the other one
-    int publish;            // 1: this kernel's last workgroup publishes the pair count (FC_PROMOTE_MEMCPY: the host reads it);
-                            // 0: the gather kernel that follows does, so this kernel ends without a device-wide ticket
+    int publish;            // 1: this kernel's last workgroup publishes the pair count and clears it (FC_PROMOTE_MEMCPY: the host reads
+                            // it); 0: the copier that follows does both, so this kernel ends without a device-wide ticket
     int32_t *host_total;    // pinned, may be NULL
     int32_t *host_total2;   // pinned scratch copy (memcpy mode reads it)
     int list_capacity;
@@ -118,7 +117,7 @@ __device__ __forceinline__ void fc_recycle_body(const fc_promote_params &p, size
         int n_ev;
         const int r_ev = fc_block_rank<THREADS>(ev, wave_cnt, n_ev);
         const int r_pr = fc_block_rank<THREADS>(pr, wave_cnt, n_prom);
-        if (tid == 0) wave_cnt[THREADS / 64] = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
+        if (tid == 0) wave_cnt[THREADS / 64] = n_prom > 0 ? atomicAdd(&p.counters[2], n_prom) : 0;
         if (ev) {
             if (pool + r_ev < p.Kmax) avail[pool + r_ev] = blk_o; else err |= FC_DEV_ERR_FREE_OVERFLOW;
             tbl[page_o] = 0;
@@ -178,7 +177,7 @@ __device__ __forceinline__ void fc_recycle_body(const fc_promote_params &p, size
             }
             n_prom += __syncthreads_count(pr);
         }
-        if (tid == 0) wave_cnt[THREADS / 64] = n_prom > 0 ? atomicAdd(&p.counters[2 + p.parity], n_prom) : 0;
+        if (tid == 0) wave_cnt[THREADS / 64] = n_prom > 0 ? atomicAdd(&p.counters[2], n_prom) : 0;
         __syncthreads();      // also makes every avail[] entry of step 1 visible
         const int list_base = wave_cnt[THREADS / 64];
 
@@ -239,10 +238,10 @@ __device__ __forceinline__ void fc_recycle_body(const fc_promote_params &p, size
         __threadfence();
         const int done = atomicAdd(&p.counters[4], 1);
         if (done == (int)(gridDim.x * gridDim.y) - 1) {
-            const int total = atomicAdd(&p.counters[2 + p.parity], 0);
+            const int total = atomicAdd(&p.counters[2], 0);
             if (p.host_total) *p.host_total = total;
             if (p.host_total2) *p.host_total2 = total;
-            p.counters[2 + (p.parity ^ 1)] = 0;
+            p.counters[2] = 0;
             p.counters[4] = 0;
         }
     }

@@ -678,7 +678,7 @@ __global__ __launch_bounds__(THREADS) void fc_select_fast_kernel(fc_rerank_param
         if (RECYCLE) {
             int err = 0;
             const int n_ev = packed_tot >> 16;
-            if (tid == 0) L.list_base = n_prom > 0 ? atomicAdd(&r.counters[2 + r.parity], n_prom) : 0;
+            if (tid == 0) L.list_base = n_prom > 0 ? atomicAdd(&r.counters[2], n_prom) : 0;
             // evicted pages, in ascending page order, hand their blocks to the tail of the available list
             int q = n_free + r_ev0;
 #pragma unroll
@@ -735,10 +735,10 @@ __global__ __launch_bounds__(THREADS) void fc_select_fast_kernel(fc_rerank_param
                 __threadfence();
                 const int done = atomicAdd(&r.counters[4], 1);
                 if (done == (int)(gridDim.x * gridDim.y) - 1) {
-                    const int total = atomicAdd(&r.counters[2 + r.parity], 0);
+                    const int total = atomicAdd(&r.counters[2], 0);
                     if (r.host_total) *r.host_total = total;
                     if (r.host_total2) *r.host_total2 = total;
-                    r.counters[2 + (r.parity ^ 1)] = 0;
+                    r.counters[2] = 0;
                     r.counters[4] = 0;
                 }
             }

@@ -379,3 +379,56 @@ def test_append_without_a_free_block_keeps_the_sequence_length():
         assert int(s.block_table[1, 1, 128]) > 0
     finally:
         s.close()
+
+
+def test_a_rerank_cycle_captured_in_a_hip_graph_replays_like_the_eager_loop():
+    """The default single-stream path (fc_rerank_promote with riding copies, the resident / promoted attention
+    pair, one merge; whole passes on the plain steps) records no event, waits for nothing on the host and
+    allocates nothing, so a whole rerank cycle can be captured in a HIP graph.  Three replays, with eager work
+    and synchronisations between them, must leave the outputs, lists, tables and free lists that the same
+    steps give eagerly in a second session."""
+    import torch
+    cfg = dataclasses.replace(synth.make_config(5, batch=3, ctx=8192, steps=32), dynamics="static")
+    R = cfg.rerank_interval
+    wl = synth.Workload(cfg)
+    eager, graphed = DecodeSession(cfg, wl), DecodeSession(cfg, wl)
+    try:
+        eager.overlap = graphed.overlap = "ride"
+        qs = torch.stack([eager.bits_to_dev(wl.queries(t)) for t in range(4 * R)])
+        stream = torch.cuda.Stream()
+        graphed.main = stream
+        graphed.copy = stream
+
+        def cycle(s, c):                                 # steps c*R .. c*R + R - 1, queries copied into the session's own buffer
+            for t in range(c * R, (c + 1) * R):
+                s.q.copy_(qs_view[t - c * R])
+                s.step(t)
+
+        with torch.cuda.stream(stream):
+            qs_view = qs[0:R]
+            cycle(graphed, 0)                            # cold fill, eagerly, on the capturing stream
+            torch.cuda.synchronize()
+            staged = torch.zeros_like(qs[0:R])           # the graph reads its queries from here
+            qs_view = staged
+            g = torch.cuda.CUDAGraph()
+            g.capture_begin()
+            cycle(graphed, 1)
+            g.capture_end()
+        torch.cuda.synchronize()
+        qs_view = qs[0:R]
+        cycle(eager, 0)
+        for c in (1, 2, 3):
+            staged.copy_(qs[c * R:(c + 1) * R])          # eager work between the replays
+            torch.cuda.synchronize()
+            g.replay()
+            qs_view = qs[c * R:(c + 1) * R]
+            cycle(eager, c)
+            torch.cuda.synchronize()
+            graphed.ctx.fc_check_device_state(stream)
+            eager.ctx.fc_check_device_state()
+            for name in ("out", "lse", "resident_pages", "resident_count", "block_table", "free_count", "promoted_count"):
+                assert torch.equal(getattr(graphed, name), getattr(eager, name)), (c, name)
+            assert torch.isfinite(graphed.out).all()
+    finally:
+        eager.close()
+        graphed.close()
