@@ -344,6 +344,8 @@ __global__ __launch_bounds__(256, 2) void fc_decode_attn_kernel(fc_attn_params p
 // One workgroup per (split item, query head).  Threads first run over the partials (maximum, then
 // weights into LDS, 256 at a time), then over the output: thread = (sub, d4) accumulates every 8th
 // partial for 4 output dims; the 8 sub-sums are combined through LDS.
+constexpr int FC_MERGE_DIRECT = 128;      // partials of one item that the merge handles with every load issued up front
+
 __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
 {
     __shared__ float wts[256];
@@ -427,6 +429,53 @@ __global__ __launch_bounds__(256) void fc_attn_merge_kernel(fc_attn_params p)
         __syncthreads();
         mstar = red[0];
         lsum = red[1];
+        if (tid < 32) {
+            float4_t r = accs[0][tid];
+#pragma unroll
+            for (int k = 1; k < 8; ++k) r += accs[k][tid];
+            *reinterpret_cast<float4_t *>(p.out + row * FC_D + 4 * tid) = r * (1.0f / lsum);
+        }
+        if (p.lse && tid == 0) p.lse[row] = (mstar + __builtin_amdgcn_logf(lsum)) * 0.6931471805599453f;
+        return;
+    }
+    if (n_parts <= FC_MERGE_DIRECT) {
+        // The same for an item split over up to 128 wavefronts (117 for an 8192-page head over 70-page shares): one
+        // partial per thread of the first two wavefronts, sixteen accumulator rows per thread in flight.
+        float4_t a4[FC_MERGE_DIRECT / 8];
+        const int rounds = (n_parts + 7) >> 3;          // the same for the whole workgroup
+#pragma unroll
+        for (int i = 0; i < FC_MERGE_DIRECT / 8; ++i) {
+            const int k = sub + 8 * i;
+            a4[i] = float4_t{0.f, 0.f, 0.f, 0.f};
+            if (i < rounds && k < n_parts)
+                a4[i] = *reinterpret_cast<const float4_t *>(p.part_acc + (slot_of(k) * p.G + g) * FC_D + 4 * d4);
+        }
+        float m = -INFINITY, l = 0.f;
+        if (tid < n_parts) {
+            const float *ml = p.part_ml + (slot_of(tid) * 16 + g) * 2;
+            m = ml[0];
+            l = ml[1];
+        }
+        float mstar = m;       // one partial per thread of the first two wavefronts
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) mstar = fmaxf(mstar, __shfl_xor(mstar, d));
+        if (lane == 0) red[wv] = mstar;
+        __syncthreads();
+        mstar = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        const float wt = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - mstar);
+        float lsum = wt * l;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) lsum += __shfl_xor(lsum, d);
+        if (tid < FC_MERGE_DIRECT) wts[tid] = wt;
+        if (lane == 0) red[4 + wv] = lsum;
+        __syncthreads();
+        lsum = (red[4] + red[5]) + (red[6] + red[7]);
+        float4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < FC_MERGE_DIRECT / 8; ++i)
+            if (i < rounds) acc += wts[sub + 8 * i] * a4[i];
+        accs[sub][d4] = acc;
+        __syncthreads();
         if (tid < 32) {
             float4_t r = accs[0][tid];
 #pragma unroll
