@@ -502,18 +502,20 @@ __device__ __forceinline__ void fc_bucket_threshold(const float (&sreg)[FC_FAST_
                     }
                     if (lane < cb && rank == rem - 1) { L.T = mk; L.need_eq = eq_before + 1; L.all_eq = eq_before + 1 == eq_all; }
                 }
-            } else if (tid < cb) {
-                const uint32_t mk = L.cand_key[tid];
-                const int mi = L.cand_idx[tid];
-                int rank = 0, eq_before = 0, eq_all = 0;
-                for (int c = 0; c < cb; ++c) {
-                    const uint32_t k = L.cand_key[c];
-                    const bool eq = k == mk, eq_lower = eq && L.cand_idx[c] < mi;
-                    rank += (k > mk || eq_lower) ? 1 : 0;
-                    eq_before += eq_lower ? 1 : 0;
-                    eq_all += eq ? 1 : 0;
+            } else {
+                for (int t = tid; t < cb; t += THREADS) {      // up to 512 candidates on 256 or 1024 threads
+                    const uint32_t mk = L.cand_key[t];
+                    const int mi = L.cand_idx[t];
+                    int rank = 0, eq_before = 0, eq_all = 0;
+                    for (int c = 0; c < cb; ++c) {
+                        const uint32_t k = L.cand_key[c];
+                        const bool eq = k == mk, eq_lower = eq && L.cand_idx[c] < mi;
+                        rank += (k > mk || eq_lower) ? 1 : 0;
+                        eq_before += eq_lower ? 1 : 0;
+                        eq_all += eq ? 1 : 0;
+                    }
+                    if (rank == rem - 1) { L.T = mk; L.need_eq = eq_before + 1; L.all_eq = eq_before + 1 == eq_all; }
                 }
-                if (rank == rem - 1) { L.T = mk; L.need_eq = eq_before + 1; L.all_eq = eq_before + 1 == eq_all; }
             }
             __syncthreads();
             T = L.T;

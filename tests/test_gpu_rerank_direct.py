@@ -129,3 +129,19 @@ def test_outliers_crowd_the_scores_into_a_few_bins(n, K, distinct, outlier):
     for ctx in (n * 16, n * 16 - 3):
         (got, ref, s), = run_case(q, row, row, ctx, K)
         assert len(np.unique(s)) >= min(distinct, 50)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_more_tied_candidates_than_threads(seed):
+    """Up to 2048 pages the selection runs on 256 threads; with four or five distinct scores the bin that holds the
+    K-th largest has 300-512 equal candidates, more than one per thread, gathered in an order that differs from run
+    to run: whichever slot the boundary candidate lands in, the threshold and the tie count must come out right."""
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(1300, 2049))
+    levels = int(rng.integers(4, 6))
+    K = int(rng.integers(20, n - 20))
+    protos_lo = ints(rng, (levels, 128), -3, 0)
+    protos_hi = protos_lo + ints(rng, (levels, 128), 0, 3)
+    which = rng.integers(0, levels, size=n)
+    q = ints(rng, (4, 128), -2, 2)
+    run_case(q, protos_lo[which][None], protos_hi[which][None], n * 16 - int(rng.integers(0, 2)) * 7, K)
