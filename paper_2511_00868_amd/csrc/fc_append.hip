@@ -176,6 +176,8 @@ extern "C" int fc_append_kv(fc_ctx *ctx, const fc_append_args *a, void *stream)
     p.seq_flags = fc_ws_ptr<int32_t>(ctx, ctx->lay.seq_flags);
     // page copies of an earlier fc_promote_pages may still be on their way into the pool (the partially filled last
     // page of a stable head among them): they land before this call writes the pool
+    FC_REQUIRE(ctx, !ctx->copies_deferred || stream == ctx->copies_stream,
+               "fc_append_kv: after FC_PROMOTE_RIDE the next call that touches the pool belongs on fc_promote_pages' main_stream");
     {
         int st = fc_launch_deferred_copies(ctx, stream);
         if (st == FC_OK) st = fc_wait_for_copies(ctx, stream);
@@ -193,6 +195,8 @@ extern "C" int fc_offload_pages(fc_ctx *ctx, const void *kv_pool, int64_t num_po
     FC_REQUIRE(ctx, kv_pool && host_pool && (pairs || n_pairs == 0), "fc_offload_pages: NULL pointer");
     FC_REQUIRE(ctx, n_pairs >= 0 && num_pool_blocks >= 2 && num_host_blocks >= 2, "fc_offload_pages: sizes out of range");
     if (n_pairs == 0) return FC_OK;
+    FC_REQUIRE(ctx, !ctx->copies_deferred || stream == ctx->copies_stream,
+               "fc_offload_pages: after FC_PROMOTE_RIDE the next call that touches the pool belongs on fc_promote_pages' main_stream");
     {   // pages being promoted into the pool land before the pool is read
         int st = fc_launch_deferred_copies(ctx, stream);
         if (st == FC_OK) st = fc_wait_for_copies(ctx, stream);
