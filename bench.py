@@ -23,10 +23,10 @@ HBM_PEAK_GBS = 8000.0
 # same counter reads for a kernel of known size in the same run): stored values, not measured by this script;
 # the summaries they come from are named beside them.
 STORED_TRAFFIC = {
-    "cfg4_ragged_b64": (3468697501, "profiles/decode_hot_path_cfg4_ragged_b64.md"),
-    "cfg2_llama8b_32k": (594110854, "profiles/decode_hot_path_cfg2_llama8b_32k.md"),
-    "cfg3_long_128k": (590848863, "profiles/decode_hot_path_cfg3_long_128k.md"),
-    "cfg5_offload_64k": (1784625573, "profiles/decode_hot_path_cfg5_offload_64k.md"),
+    "cfg4_ragged_b64": (3468703135, "profiles/decode_hot_path_cfg4_ragged_b64.md"),
+    "cfg2_llama8b_32k": (594121102, "profiles/decode_hot_path_cfg2_llama8b_32k.md"),
+    "cfg3_long_128k": (590859109, "profiles/decode_hot_path_cfg3_long_128k.md"),
+    "cfg5_offload_64k": (1784639509, "profiles/decode_hot_path_cfg5_offload_64k.md"),
 }
 MIN_BRACKETED_LAUNCHES = 32
 
