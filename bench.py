@@ -304,6 +304,9 @@ def run_workload(args, index: int, torch, *, main_workload: bool):
     }
     if main_workload and not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_budget, args.paper_unstable_topk)
+    elif cfg.index == 2 and not args.no_cpu_baseline:
+        # the 32k workload is small enough for a single-thread figure beside the all-cores one (a third of the budget)
+        res["cpu_baseline"] = cpu_baseline(cfg, wl, args.cpu_budget / 3, args.paper_unstable_topk)
     sess.close()
     del sess, q_all, new_kv, wl
     torch.cuda.empty_cache()
@@ -371,6 +374,8 @@ def main():
             "attn_plus_rerank_GBps_excl_promotion": r["attn_plus_rerank_GBps_excl_promotion"],
             "promoted_MB_last_rerank": r["promoted_MB_last_rerank"],
         }
+        if "cpu_baseline" in r:
+            others[r["config"]["workload"]]["cpu_baseline"] = r["cpu_baseline"]
     if others:
         out["workloads"] = others
     out["parity_coverage"] = ("tests/test_gpu_parity.py runs every workload above at full size in this launch configuration and "
