@@ -132,7 +132,7 @@ def run_workload(args, index: int, torch, *, main_workload: bool):
     diag_steps = min(args.steps, 32)     # per diagnostic pass; with --append both passes append
     if args.append:
         import dataclasses
-        cfg = dataclasses.replace(cfg, append_tokens=total_steps + 2 * diag_steps, dynamics="static")
+        cfg = dataclasses.replace(cfg, append_tokens=total_steps + 3 * diag_steps, dynamics="static")
     t_gen = time.perf_counter()
     wl = synth.Workload(cfg)
     mode = binding.FC_PROMOTE_GATHER if args.promote_mode == "gather" else binding.FC_PROMOTE_MEMCPY
@@ -140,7 +140,7 @@ def run_workload(args, index: int, torch, *, main_workload: bool):
     q_all = torch.stack([sess.bits_to_dev(wl.queries(t)) for t in range(total_steps)])
     new_kv = None
     if args.append:
-        toks = [wl.append(t) for t in range(total_steps + 2 * diag_steps)]
+        toks = [wl.append(t) for t in range(total_steps + 3 * diag_steps)]
         new_kv = (torch.stack([sess.bits_to_dev(k) for k, _ in toks]), torch.stack([sess.bits_to_dev(v) for _, v in toks]))
     n_appended = [0]
     torch.cuda.synchronize()
@@ -209,6 +209,17 @@ def run_workload(args, index: int, torch, *, main_workload: bool):
             rr_us.append(ev["rerank_begin"].elapsed_time(ev["rerank_end"]) * 1e3)
             pr_us.append(ev["rerank_end"].elapsed_time(ev["recycle_end"]) * 1e3)
             cp_us.append(ev["recycle_end"].elapsed_time(ev["copies_end"]) * 1e3)
+    # ... and the chain in front of the page copies as the timed region runs it: fc_rerank_promote, one call
+    chain_us = []
+    if sess.fused_rerank:
+        for t in range(diag):
+            tt = t % total_steps
+            rer = cfg.is_rerank_step(tt) and any(cfg.stable)
+            sess.events = {k: torch.cuda.Event(enable_timing=True) for k in ("chain_begin", "chain_end")} if rer else None
+            run_step(tt)
+            if rer:
+                torch.cuda.synchronize()
+                chain_us.append(sess.events["chain_begin"].elapsed_time(sess.events["chain_end"]) * 1e3)
     sess.events = None
     promoted_last = int(sess.total_promoted[0])
 
@@ -273,6 +284,8 @@ def run_workload(args, index: int, torch, *, main_workload: bool):
                                                  if plain_us and rr_us else None,
         "rerank_topk_us_per_invocation": med(rr_us),
         "rerank_topk_us_per_step_amortised": round(float(np.median(rr_us)) / cfg.rerank_interval, 2) if rr_us else None,
+        # fc_rerank_promote (scoring, then selection and block recycling in one kernel), bracketed by two events
+        "rerank_promote_us_per_invocation": med(chain_us),
         # with the copies in line the recycling kernel and the copies are one enqueue on one stream: only their sum is
         # seen; when they ride in an attention launch, "page copies" is that whole launch (resident pages + copies)
         "recycle_us_per_invocation": med(pr_us) if pr_us and (ride or not inline) else None,
@@ -370,6 +383,7 @@ def main():
             "step_us_plain_median": r["step_us_plain_median"], "step_us_rerank_median": r["step_us_rerank_median"],
             "rerank_topk_us_per_invocation": r["rerank_topk_us_per_invocation"],
             "rerank_topk_us_per_step_amortised": r["rerank_topk_us_per_step_amortised"],
+            "rerank_promote_us_per_invocation": r["rerank_promote_us_per_invocation"],
             "recycle_and_page_copies_us_per_invocation": r["recycle_and_page_copies_us_per_invocation"],
             "attn_plus_rerank_GBps_excl_promotion": r["attn_plus_rerank_GBps_excl_promotion"],
             "promoted_MB_last_rerank": r["promoted_MB_last_rerank"],

@@ -245,8 +245,12 @@ class DecodeSession:
     def _rerank_and_promote(self, copy, pmode):
         """Score, select, recycle and the page copies (or, with FC_PROMOTE_RIDE, only their description)."""
         ev = self.events
-        if self.fused_rerank and ev is None:
+        if self.fused_rerank and (ev is None or "chain_begin" in ev):
+            if ev is not None:
+                ev["chain_begin"].record(self.main)
             self.rerank_promote(copy_stream=copy, mode=pmode)
+            if ev is not None:
+                ev["chain_end"].record(self.main)
             return
         if ev is not None:
             ev["rerank_begin"].record(self.main)
@@ -262,7 +266,7 @@ class DecodeSession:
     def _attend_pair(self, first: int, second: int, first_stream=None, carries_copies=False):
         """The two attention calls of a split pass; with riding copies the first launch carries them."""
         self.attend(first, stream=first_stream)
-        if self.events is not None and carries_copies:
+        if self.events is not None and carries_copies and "copies_end" in self.events:
             self.events["copies_end"].record(self.main)     # the launch that carried the copies has ended
         self.attend(second)
 
