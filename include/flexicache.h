@@ -193,7 +193,7 @@ typedef struct {
 int fc_promote_pages(fc_ctx *ctx, const fc_promote_args *args, void *main_stream, void *side_stream);
 
 /* fc_rerank_topk followed by fc_promote_pages as one call, with the same results bit for bit.  Up to 8192 pages per
- * sequence and a page budget of up to 4096 the selection of a head and the recycling of its blocks then run in one
+ * sequence and a page budget (max_topk) of up to 12288 the selection of a head and the recycling of its blocks then run in one
  * kernel (the fused recycling kernel of Sec. 3.4 "Physical Block Reuse During Reranking"), which takes two launches
  * and one trip of the new lists through memory off the path to the page copies; other shapes run the same kernels
  * as the two separate calls.  rerank->topk_pages / topk_count must be promote->new_pages / new_count, and batch,
