@@ -176,8 +176,11 @@ extern "C" int fc_destroy(fc_ctx *ctx)
     (void)hipEventDestroy(ctx->ev_diff_done);
     (void)hipEventDestroy(ctx->ev_copies_done);
     (void)hipEventDestroy(ctx->ev_first_done);
-    for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
-        if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
+    if (ctx->prof_ev) {
+        for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
+            if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
+        free(ctx->prof_ev);
+    }
     delete ctx;
     return FC_OK;
 }
@@ -221,6 +224,10 @@ extern "C" int fc_profile_begin(fc_ctx *ctx, int32_t every_nth, void *stream)
 {
     if (!ctx || every_nth < 1) return FC_ERR_INVALID_ARG;
     hipStream_t s = (hipStream_t)stream;
+    if (!ctx->prof_ev) {
+        ctx->prof_ev = (hipEvent_t *)calloc(2 * FC_MAX_PROFILE_EVENTS, sizeof(hipEvent_t));
+        if (!ctx->prof_ev) return fc_fail(ctx, FC_ERR_INVALID_ARG, "fc_profile_begin: out of host memory");
+    }
     for (int i = 0; i < 2 * FC_MAX_PROFILE_EVENTS; ++i)
         if (!ctx->prof_ev[i]) FC_HIP(ctx, hipEventCreate(&ctx->prof_ev[i]));
     // what the bracket itself costs: event, empty kernel, event

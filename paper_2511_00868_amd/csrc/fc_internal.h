@@ -118,7 +118,7 @@ struct fc_ctx {
     int prof_used;
     int prof_stride, prof_seen;
     double prof_empty_ms;
-    hipEvent_t prof_ev[2 * FC_MAX_PROFILE_EVENTS];
+    hipEvent_t *prof_ev;  // 2 * FC_MAX_PROFILE_EVENTS events, created by the first fc_profile_begin (benchmarks only)
     char err[512];
 };
 
